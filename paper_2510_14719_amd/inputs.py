@@ -1,0 +1,115 @@
+"""Seeded synthetic inputs for the attention-forward workloads.
+
+This module holds none of the method's arithmetic: it draws random numbers,
+rounds them to 16-bit storage and returns raw ``uint16`` bit patterns, so the
+CPU oracle and the GPU library are fed identical bits.  It is the only module
+both sides' tests import.
+
+The paper's attention sweep (Section 5.4: batch 4, head dimension 128, sequence
+lengths 1024..16384, causal and non-causal, fp16) uses no dataset; attention
+throughput does not depend on the values, so i.i.d. N(0,1) tensors of the same
+shapes stand in for it.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+FP16 = 0
+BF16 = 1
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    B: int
+    H: int
+    N: int
+    d: int
+    dtype: int          # FP16 or BF16
+    causal: bool
+    peaky: bool = False  # 5 % of the K rows of every head multiplied by 8
+    seed: int = 0
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / float(np.sqrt(self.d))
+
+    @property
+    def flops(self) -> float:
+        """Credited work: 4*B*H*N^2*d, halved when causal."""
+        f = 4.0 * self.B * self.H * float(self.N) ** 2 * self.d
+        return f / 2 if self.causal else f
+
+
+# The five configurations of the benchmark definition (C2 in both variants).
+WORKLOADS = {
+    "c1": Workload("c1", 1, 2, 128, 64, FP16, False, seed=1000),
+    "c2": Workload("c2", 16, 16, 1024, 64, FP16, False, seed=2000),
+    "c2_causal": Workload("c2_causal", 16, 16, 1024, 64, FP16, True, seed=2000),
+    "c3": Workload("c3", 4, 16, 4096, 128, BF16, False, seed=3000),
+    "c4": Workload("c4", 1, 16, 16384, 128, FP16, False, seed=4000),
+    "c5": Workload("c5", 2, 32, 8192, 128, BF16, True, peaky=True, seed=5000),
+}
+
+
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """float32 -> IEEE binary16 bit patterns, round to nearest even."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """float32 -> bfloat16 bit patterns, round to nearest even (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    return ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
+
+
+def to_bits(x: np.ndarray, dtype: int) -> np.ndarray:
+    return f32_to_bf16_bits(x) if dtype == BF16 else f32_to_f16_bits(x)
+
+
+def normal_bits(shape, dtype: int, seed: int, std: float = 1.0) -> np.ndarray:
+    """i.i.d. N(0, std^2) drawn in float32 from Philox(seed), rounded to 16 bit."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    x = rng.standard_normal(size=shape, dtype=np.float32)
+    if std != 1.0:
+        x *= np.float32(std)
+    return to_bits(x, dtype)
+
+
+def make_qkv(B: int, H: int, N: int, d: int, dtype: int, seed: int, peaky: bool = False,
+             peak_frac: float = 0.05, peak_gain: float = 8.0):
+    """Q, K, V as ``[B,H,N,d]`` uint16 bit patterns; seeds ``seed, seed+1, seed+2``.
+
+    With ``peaky`` a fixed seeded choice of ``floor(peak_frac*N)`` distinct key
+    rows of every (b, h) is multiplied by ``peak_gain`` in float32 before the
+    rounding, which makes the softmax rows close to one-hot.
+    """
+    shape = (B, H, N, d)
+    q = normal_bits(shape, dtype, seed)
+    v = normal_bits(shape, dtype, seed + 2)
+    rng = np.random.Generator(np.random.Philox(seed + 1))
+    kf = rng.standard_normal(size=shape, dtype=np.float32)
+    if peaky:
+        n_peak = int(np.floor(peak_frac * N))
+        for b in range(B):
+            for h in range(H):
+                idx = rng.permutation(N)[:n_peak]
+                kf[b, h, idx, :] *= np.float32(peak_gain)
+    k = to_bits(kf, dtype)
+    return q, k, v
+
+
+def make_workload(w: Workload):
+    return make_qkv(w.B, w.H, w.N, w.d, w.dtype, w.seed, peaky=w.peaky)
+
+
+def sample_rows(B: int, H: int, N: int, n: int, seed: int, always=()):
+    """``n`` seeded (b, h, i) triples plus the fixed ones in ``always`` (deduplicated)."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    rows = {tuple(int(x) for x in r) for r in always}
+    while len(rows) < n + len(always):
+        rows.add((int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(N))))
+    return sorted(rows)
