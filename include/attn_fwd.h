@@ -1,0 +1,94 @@
+/*
+ * attn_fwd.h -- C ABI of the gfx950 (MI355X) fused attention forward library.
+ *
+ * The operation (the paper's Section 3.4.2 names its three stages per key/value
+ * tile: T = Q K^T on the matrix cores, C = softmax on the vector ALU, U = P V on
+ * the matrix cores; Section 5.4 names the workload, causal and non-causal
+ * multi-head attention):
+ *
+ *     for every batch b and head h, with q_i, k_j, v_j the rows of Q, K, V:
+ *       s_ij  = scale * <q_i, k_j>            (causal: key j is visible to query i iff j <= i)
+ *       O_i   = sum_j softmax_j(s_ij) * v_j
+ *       LSE_i = ln sum_j exp(s_ij)            (natural log of the scaled, masked scores)
+ *
+ * computed by a single kernel with a streaming (online) softmax: the N x N
+ * score matrix is never written to memory.
+ *
+ * Arguments (identical for every entry point):
+ *   q, k, v  DEVICE pointers, read only.  Layout [B][H][N][d], contiguous, d
+ *            fastest, 16-bit elements (IEEE binary16 or bfloat16).
+ *   o        DEVICE pointer, written.  Same layout and element type as q.  Every
+ *            element is overwritten.  Must not overlap q, k or v.
+ *   lse      DEVICE pointer, written.  Layout [B][H][N], float32.
+ *   B, H     batch size and number of heads, >= 1.
+ *   N        sequence length (queries = keys), >= 1; any value, no multiple required.
+ *   d        head dimension, 64 or 128.
+ *   scale    multiplies the raw dot products; finite and > 0.
+ *   causal   0: every key visible; non-zero: key j visible to query i iff j <= i.
+ *   stream   a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * All five pointers must be 16-byte aligned.  The caller owns every buffer; the
+ * library allocates nothing, retains nothing and never synchronises: a call
+ * validates its arguments on the host, enqueues one kernel on `stream` on the
+ * current device and returns.  Calls are thread safe.
+ *
+ * Return value: ATTN_FWD_OK or a negative error code; attn_fwd_strerror gives
+ * its text.  Argument validation happens before any HIP call, so the argument
+ * errors can be provoked on a machine without a GPU.  Nothing is enqueued when
+ * an error is returned.
+ */
+#ifndef ATTN_FWD_H
+#define ATTN_FWD_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ATTN_FWD_OK = 0,
+    ATTN_FWD_ERR_NULL = -1,       /* a pointer argument is NULL */
+    ATTN_FWD_ERR_SHAPE = -2,      /* B, H or N < 1, or d not in {64, 128}, or unknown dtype */
+    ATTN_FWD_ERR_SCALE = -3,      /* scale is NaN, infinite, zero or negative */
+    ATTN_FWD_ERR_ALIGN = -4,      /* a pointer is not 16-byte aligned */
+    ATTN_FWD_ERR_OVERFLOW = -5,   /* B*H*N*d does not fit the kernel's 32-bit element indexing */
+    ATTN_FWD_ERR_LAUNCH = -6,     /* the HIP runtime refused the launch */
+    ATTN_FWD_ERR_ALIAS = -7       /* o overlaps q, k or v */
+};
+
+enum { ATTN_FWD_FP16 = 0, ATTN_FWD_BF16 = 1 };
+
+/* Q, K, V, O in IEEE binary16. */
+int attn_fwd_f16(const void *q, const void *k, const void *v, void *o, float *lse,
+                 int B, int H, int N, int d, float scale, int causal, void *stream);
+
+/* Q, K, V, O in bfloat16. */
+int attn_fwd_bf16(const void *q, const void *k, const void *v, void *o, float *lse,
+                  int B, int H, int N, int d, float scale, int causal, void *stream);
+
+/* Same call with the element type as an argument (ATTN_FWD_FP16 / ATTN_FWD_BF16). */
+int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
+             int B, int H, int N, int d, float scale, int causal, void *stream, int dtype);
+
+/* Host-only argument check: what the entry points above would return before launching. */
+int attn_fwd_check_args(const void *q, const void *k, const void *v, const void *o, const float *lse,
+                        int B, int H, int N, int d, float scale, int dtype);
+
+/* Static, NUL-terminated description of a return code.  Never NULL. */
+const char *attn_fwd_strerror(int code);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int attn_fwd_version(void);
+
+/*
+ * Name of a launch parameter of the kernel chosen for (d, causal) and its value,
+ * for benchmark reports: which = 0 query rows per workgroup (BM), 1 keys per
+ * step (BN), 2 LDS stages, 3 threads per workgroup.  Returns -1 for an unknown
+ * `which` or unsupported d.
+ */
+int attn_fwd_tile_param(int d, int causal, int which);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* ATTN_FWD_H */

@@ -1,0 +1,125 @@
+"""Thin ctypes binding of ``libattn_fwd.so`` (the C ABI of ``include/attn_fwd.h``).
+
+Argument marshalling only: every step of the attention forward pass runs in the
+HIP kernels behind the C ABI.  Torch tensors are accepted for their device
+memory (``data_ptr()``) and the current stream handle; nothing is computed in
+Python and there is no fallback: without the built library, or without a GPU
+for the tensors, the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libattn_fwd.so")
+
+FP16 = 0
+BF16 = 1
+
+_lib = None
+
+
+class AttnFwdError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("attn_fwd failed with code %d: %s" % (code, text))
+        self.code = code
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_2510_14719_amd.build` "
+                "(there is no CPU fallback)" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, fp, ci, cf = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+        common = [vp, vp, vp, vp, fp, ci, ci, ci, ci, cf, ci, vp]
+        lib.attn_fwd_f16.restype = ci
+        lib.attn_fwd_f16.argtypes = common
+        lib.attn_fwd_bf16.restype = ci
+        lib.attn_fwd_bf16.argtypes = common
+        lib.attn_fwd.restype = ci
+        lib.attn_fwd.argtypes = common + [ci]
+        lib.attn_fwd_check_args.restype = ci
+        lib.attn_fwd_check_args.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, cf, ci]
+        lib.attn_fwd_strerror.restype = ctypes.c_char_p
+        lib.attn_fwd_strerror.argtypes = [ci]
+        lib.attn_fwd_version.restype = ci
+        lib.attn_fwd_version.argtypes = []
+        lib.attn_fwd_tile_param.restype = ci
+        lib.attn_fwd_tile_param.argtypes = [ci, ci, ci]
+        _lib = lib
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return load_library().attn_fwd_strerror(int(code)).decode()
+
+
+def _ptr(x) -> int:
+    """Device address of a torch tensor, or an integer address passed through."""
+    if isinstance(x, int):
+        return x
+    if not x.is_cuda:
+        raise ValueError("attn_fwd takes device tensors; got a tensor on %s" % x.device)
+    if not x.is_contiguous():
+        raise ValueError("attn_fwd takes contiguous [B,H,N,d] tensors")
+    return x.data_ptr()
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def attn_fwd_raw(q, k, v, o, lse, B, H, N, d, scale, causal, stream, dtype) -> int:
+    """The C call itself; returns its code without raising."""
+    return int(load_library().attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), int(B), int(H), int(N), int(d),
+                                       float(scale), int(bool(causal)), _stream_handle(stream), int(dtype)))
+
+
+def attn_fwd(q, k, v, o, lse, B, H, N, d, scale, causal, stream=None, dtype=None) -> None:
+    """``attn_fwd(q, k, v, o, lse, B, H, N, d, scale, causal, stream)`` of the C ABI.
+
+    ``dtype`` defaults to the element type of ``q`` (float16 -> FP16, bfloat16 or
+    a 16-bit integer view needs an explicit ``dtype``).  Asynchronous: the kernel
+    is enqueued on ``stream`` (default: torch's current stream) and the call returns.
+    """
+    if dtype is None:
+        import torch
+        if q.dtype == torch.float16:
+            dtype = FP16
+        elif q.dtype == torch.bfloat16:
+            dtype = BF16
+        else:
+            raise ValueError("pass dtype=FP16/BF16 for tensors of type %s" % q.dtype)
+    rc = attn_fwd_raw(q, k, v, o, lse, B, H, N, d, scale, causal, stream, dtype)
+    if rc != 0:
+        raise AttnFwdError(rc, strerror(rc))
+
+
+def attn_fwd_f16(q, k, v, o, lse, B, H, N, d, scale, causal, stream=None) -> None:
+    rc = int(load_library().attn_fwd_f16(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), int(B), int(H), int(N), int(d),
+                                         float(scale), int(bool(causal)), _stream_handle(stream)))
+    if rc != 0:
+        raise AttnFwdError(rc, strerror(rc))
+
+
+def attn_fwd_bf16(q, k, v, o, lse, B, H, N, d, scale, causal, stream=None) -> None:
+    rc = int(load_library().attn_fwd_bf16(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), int(B), int(H), int(N), int(d),
+                                          float(scale), int(bool(causal)), _stream_handle(stream)))
+    if rc != 0:
+        raise AttnFwdError(rc, strerror(rc))
+
+
+def tile_params(d: int, causal: bool = False) -> dict:
+    lib = load_library()
+    return {"BM": lib.attn_fwd_tile_param(d, int(causal), 0), "BN": lib.attn_fwd_tile_param(d, int(causal), 1),
+            "stages": lib.attn_fwd_tile_param(d, int(causal), 2), "threads": lib.attn_fwd_tile_param(d, int(causal), 3)}

@@ -1,0 +1,35 @@
+// Internal seam between the host-side C ABI (attn_api.cpp) and the kernels (attn_fwd_kernel.hip).
+#pragma once
+
+// Tile configuration compiled into the library.
+#ifndef ATTN_CFG_NW
+#define ATTN_CFG_NW 8        // waves per workgroup
+#endif
+#ifndef ATTN_CFG_MB
+#define ATTN_CFG_MB 1        // 32-query blocks per wave
+#endif
+#ifndef ATTN_CFG_BN
+#define ATTN_CFG_BN 64       // keys per K/V tile
+#endif
+#ifndef ATTN_CFG_STAGES
+#define ATTN_CFG_STAGES 3    // LDS ring depth
+#endif
+
+struct AttnLaunchArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* o;
+    float* lse;
+    int B, H, N, d;
+    float scale;
+    int causal;
+    int dtype;      // 0 = fp16, 1 = bf16
+    void* stream;   // hipStream_t
+};
+
+// Enqueue the kernel for already-validated arguments.  0 on success, -1 if HIP refused the launch.
+int attn_launch(const AttnLaunchArgs& a);
+
+// Query rows per workgroup (0), keys per tile (1), LDS stages (2), threads per workgroup (3).
+int attn_launch_tile_param(int d, int causal, int which);

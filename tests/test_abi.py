@@ -1,0 +1,74 @@
+"""The C-ABI library loads on a machine without a GPU, exports every symbol the header
+declares, and rejects bad arguments before touching HIP."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "attn_fwd.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2510_14719_amd import binding
+    return binding.load_library()
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(attn_fwd\w*)\s*\(", src)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_functions()
+    assert {"attn_fwd", "attn_fwd_f16", "attn_fwd_bf16", "attn_fwd_strerror", "attn_fwd_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), "library does not export %s" % n
+
+
+def test_version_and_strerror(lib):
+    assert lib.attn_fwd_version() >= 100
+    for code in range(-8, 1):
+        text = lib.attn_fwd_strerror(code)
+        assert text and len(text) > 3
+    assert lib.attn_fwd_strerror(0) == b"success"
+
+
+def test_tile_params(lib):
+    for d in (64, 128):
+        bm, bn, st, th = (lib.attn_fwd_tile_param(d, 0, w) for w in range(4))
+        assert bm % 32 == 0 and bn % 32 == 0 and st >= 3 and th % 64 == 0
+        assert st * 2 * bn * d * 2 <= 160 * 1024   # the LDS ring fits one CU
+    assert lib.attn_fwd_tile_param(96, 0, 0) == -1
+    assert lib.attn_fwd_tile_param(128, 0, 9) == -1
+
+
+def test_argument_validation_needs_no_gpu(lib):
+    # fake, aligned, non-overlapping addresses: validation never dereferences them
+    q, k, v, o, l = 0x10000000, 0x20000000, 0x30000000, 0x40000000, 0x50000000
+    f = lib.attn_fwd_check_args
+    ok = (q, k, v, o, l, 2, 4, 1024, 128, 0.088, 0)
+    assert f(*ok) == 0
+    assert f(0, k, v, o, l, 2, 4, 1024, 128, 0.088, 0) == -1
+    assert f(q, k, v, o, 0, 2, 4, 1024, 128, 0.088, 0) == -1
+    assert f(q, k, v, o, l, 0, 4, 1024, 128, 0.088, 0) == -2
+    assert f(q, k, v, o, l, 2, 4, 0, 128, 0.088, 0) == -2
+    assert f(q, k, v, o, l, 2, 4, 1024, 96, 0.088, 0) == -2
+    assert f(q, k, v, o, l, 2, 4, 1024, 128, 0.088, 2) == -2
+    for bad in (0.0, -1.0, float("nan"), float("inf")):
+        assert f(q, k, v, o, l, 2, 4, 1024, 128, bad, 0) == -3
+    assert f(q + 8, k, v, o, l, 2, 4, 1024, 128, 0.088, 0) == -4
+    assert f(q, k, v, o, l + 4, 2, 4, 1024, 128, 0.088, 0) == -4
+    assert f(q, k, v, o, l, 1, 1, 2 ** 23, 128, 0.088, 0) == -5
+    assert f(q, k, v, q, l, 2, 4, 1024, 128, 0.088, 0) == -7
+    assert f(q, k, v, k + 16, l, 2, 4, 1024, 128, 0.088, 0) == -7
+
+
+def test_entry_points_return_argument_errors_without_launching(lib):
+    # the full entry points run the same validation first; with a NULL pointer no HIP call is made
+    assert lib.attn_fwd_f16(None, None, None, None, None, 1, 1, 64, 64, 0.125, 0, None) == -1
+    assert lib.attn_fwd_bf16(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 1, 1, 64, 48, 0.125, 0, None) == -2
+    assert lib.attn_fwd(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 1, 1, 64, 64, 0.125, 0, None, 7) == -2
