@@ -34,6 +34,10 @@ def load_library() -> ctypes.CDLL:
             raise ImportError(
                 "%s is missing: build it with `python -m paper_2510_14719_amd.build` "
                 "(there is no CPU fallback)" % LIB_PATH)
+        # PyTorch provides the device memory and the streams, so its HIP runtime must be the one
+        # this process uses: load it first, and the library's libamdhip64 dependency resolves to
+        # the copy torch has already mapped instead of a second runtime with its own streams.
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         vp, fp, ci, cf = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float
         common = [vp, vp, vp, vp, fp, ci, ci, ci, ci, cf, ci, vp]

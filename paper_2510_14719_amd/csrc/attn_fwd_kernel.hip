@@ -348,20 +348,25 @@ int launch(const AttnLaunchArgs& a)
     auto kern = attn_fwd_kernel<DTYPE, D, NW, MB, BN, STAGES, CAUSAL>;
     static bool attr_set = false;   // idempotent; a race only repeats the call
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) {
-            (void)hipGetLastError();
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
             return -1;
-        }
         attr_set = true;
     }
     const int nqt = (a.N + BM - 1) / BM;
     const long long total = (long long)nqt * a.B * a.H;
     const float log2e = 1.4426950408889634f;
-    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(NW * 64), smem, (hipStream_t)a.stream,
-                       (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, (uint16_t*)a.o, a.lse,
-                       a.N, nqt, (int)total, a.scale, a.scale * log2e);
-    if (hipGetLastError() != hipSuccess) return -1;
-    return 0;
+    const uint16_t* q = (const uint16_t*)a.q;
+    const uint16_t* k = (const uint16_t*)a.k;
+    const uint16_t* v = (const uint16_t*)a.v;
+    uint16_t* o = (uint16_t*)a.o;
+    float* lse = a.lse;
+    int N = a.N, nqt_arg = nqt, total_arg = (int)total;
+    float scale = a.scale, scale_log2e = a.scale * log2e;
+    void* args[] = {&q, &k, &v, &o, &lse, &N, &nqt_arg, &total_arg, &scale, &scale_log2e};
+    // the launch's own status, not hipGetLastError(): that one also reports stale errors of unrelated calls
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3((unsigned)total), dim3(NW * 64),
+                                         args, smem, (hipStream_t)a.stream);
+    return e == hipSuccess ? 0 : -1;
 }
 
 template <int DTYPE, int D>
