@@ -20,6 +20,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "attn_launch.h"
 
 namespace {
@@ -32,6 +34,17 @@ typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 #define LDS_AS __attribute__((address_space(3)))
+
+// The softmax reference moves only when a row maximum grew by more than this many powers of two.
+constexpr float RESCALE_LOG2 = 8.0f;
+
+// Tuning knobs of the hand-interleaved pipeline (see tile_step).
+#ifndef ATTN_KWIN
+#define ATTN_KWIN 3
+#endif
+#ifndef ATTN_VWIN
+#define ATTN_VWIN 3
+#endif
 
 // Element-type traits: MFMA flavour and fp32 -> 16-bit conversion (round to nearest even).
 template <int DTYPE> struct Elem;
@@ -107,7 +120,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 {
     typedef Elem<DTYPE> E;
     constexpr int BM = NW * MB * 32;            // query rows per workgroup
-    constexpr int KB = BN / 32;                 // 32-key blocks per K/V tile
+    constexpr int KB = BN / 32;                 // 32-key blocks ("halves") per K/V tile
     constexpr int KK = D / 16;                  // contraction steps of Q K^T
     constexpr int DB = D / 32;                  // 32-wide feature blocks of O
     constexpr int ROW_BYTES = D * 2;
@@ -117,7 +130,8 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int CHUNKS = TILE_BYTES / 1024;   // 1 KiB wave-transfers per tile
     constexpr int CPW = CHUNKS / NW;            // ... per wave
     static_assert(CHUNKS % NW == 0, "tile must split evenly over the waves");
-    static_assert(STAGES >= 3, "prefetch distance 2 needs three stages");
+    static_assert(STAGES == 4, "the ring protocol below keeps tiles j..j+3 in four stages");
+    static_assert(KB == 2, "a tile is processed as two 32-key halves");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const unsigned lds_base = (unsigned)(size_t)(LDS_AS void*)smem;
@@ -136,50 +150,62 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 
     const size_t head_off = (size_t)bh * N * D;
     const uint16_t* qh = q + head_off;
-    const uint16_t* kh = k + head_off;
-    const uint16_t* vh = v + head_off;
+    const char* kh = reinterpret_cast<const char*>(k + head_off);
+    const char* vh = reinterpret_cast<const char*>(v + head_off);
 
-    // ---- number of K/V tiles
+    // ---- number of K/V tiles the workgroup walks, and of 32-key halves this wave computes on
     int nt = (N + BN - 1) / BN;
     if (CAUSAL) {
         const int last_q = min(q0 + BM, N) - 1;
         nt = min(nt, last_q / BN + 1);
     }
+    int nh_w = min(2 * nt, (N + 31) / 32);                              // halves that hold a real key
+    if (CAUSAL) nh_w = min(nh_w, (wq0 + MB * 32 - 1) / 32 + 1);         // ... and one this wave's rows can see
 
-    // ---- per-lane constants of the global -> LDS copies
+    // ---- global -> LDS copies.  A wave moves CPW 1 KiB pieces of K and of V per tile.
     // K tile in LDS: [feature group of 32][16-row block][16-byte column of the group (4)][row (16)][16 B]
     // V tile in LDS: [feature group of 32][row (BN)][64 B]
-    int k_row[CPW], k_col[CPW], v_row[CPW], v_col[CPW];
-    unsigned k_dst[CPW], v_dst[CPW];
-#pragma unroll
-    for (int i = 0; i < CPW; ++i) {
-        const int wc = wave * CPW + i;
-        const int fg = wc / RB, rb = wc % RB;
-        k_row[i] = rb * 16 + (lane & 15);
-        k_col[i] = (fg * 4 + (lane >> 4)) * 16;
-        v_row[i] = rb * 16 + (lane >> 2);
-        v_col[i] = fg * 64 + (lane & 3) * 16;
-        k_dst[i] = lds_base + wc * 1024;
-        v_dst[i] = lds_base + TILE_BYTES + wc * 1024;
-    }
+    // Lane L of a K piece fetches row L%16, column L/16 of the piece's (16 rows x 64 B) source block; of
+    // a V piece row L/4, column L%4.  Inside the sequence the per-lane offset is a constant and the
+    // tile/piece offset is added to the scalar base; the clamped form serves the tile that overruns N.
+    const unsigned k_lane_off = (lane & 15) * ROW_BYTES + (lane >> 4) * 16;
+    const unsigned v_lane_off = (lane >> 2) * ROW_BYTES + (lane & 3) * 16;
     auto issue_tile = [&](int t, int stage) {
         const int kv0 = t * BN;
-        const unsigned sbase = stage * STAGE_BYTES;
+        const unsigned sbase = lds_base + stage * STAGE_BYTES;
+        if (kv0 + BN <= N) {
 #pragma unroll
-        for (int i = 0; i < CPW; ++i) {
-            const int rk = min(kv0 + k_row[i], N - 1);
-            dma16(kh, (unsigned)(rk * ROW_BYTES + k_col[i]), k_dst[i] + sbase);
-        }
+            for (int i = 0; i < CPW; ++i) {
+                const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
+                const size_t off = (size_t)(kv0 + rb * 16) * ROW_BYTES + fg * 64;
+                dma16(kh + off, k_lane_off, sbase + wc * 1024);
+            }
 #pragma unroll
-        for (int i = 0; i < CPW; ++i) {
-            const int rv = min(kv0 + v_row[i], N - 1);
-            dma16(vh, (unsigned)(rv * ROW_BYTES + v_col[i]), v_dst[i] + sbase);
+            for (int i = 0; i < CPW; ++i) {
+                const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
+                const size_t off = (size_t)(kv0 + rb * 16) * ROW_BYTES + fg * 64;
+                dma16(vh + off, v_lane_off, sbase + TILE_BYTES + wc * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) {
+                const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
+                const int row = min(kv0 + rb * 16 + (lane & 15), N - 1);
+                dma16(kh, (unsigned)(row * ROW_BYTES + fg * 64 + (lane >> 4) * 16), sbase + wc * 1024);
+            }
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) {
+                const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
+                const int row = min(kv0 + rb * 16 + (lane >> 2), N - 1);
+                dma16(vh, (unsigned)(row * ROW_BYTES + fg * 64 + (lane & 3) * 16), sbase + TILE_BYTES + wc * 1024);
+            }
         }
     };
 
-    // ---- prologue: two tiles in flight, Q fragments into registers
+    // ---- prologue: up to three tiles in flight, Q fragments into registers
     issue_tile(0, 0);
     if (nt > 1) issue_tile(1, 1);
+    if (nt > 2) issue_tile(2, 2);
 
     s16x8 Qf[MB][KK];
 #pragma unroll
@@ -190,9 +216,16 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         for (int kk = 0; kk < KK; ++kk)
             Qf[mb][kk] = *reinterpret_cast<const s16x8*>(qr + (kk * 2 + g) * 8);
     }
+    // Use the Q fragments once here: the compiler then waits for their loads before the loop instead
+    // of inside it, where its vmcnt(0) would also wait for the K/V copies issued a moment earlier.
+    // (The Q loads were issued after the tile copies, so this wait also covers tiles 0..2.)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) asm volatile("" :: "v"(Qf[mb][kk]));
 
     f32x16 O[MB][DB];
-    float m_run[MB], l_run[MB];
+    float m_run[MB], l_run[MB], alpha[MB], neg_mc[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         m_run[mb] = -__builtin_inff();
@@ -202,118 +235,243 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 #pragma unroll
             for (int i = 0; i < 16; ++i) O[mb][db][i] = 0.f;
     }
+    bool any_upd = false;
 
     // per-lane LDS read offsets (the rest of every address is an immediate)
     const int k_lane = (lr >> 4) * 1024 + g * 256 + (lr & 15) * 16;
     const int v_lane = TILE_BYTES + (4 * g + ((lane & 15) >> 2)) * 64 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
 
-    int stage = 0;
-    for (int j = 0; j < nt; ++j) {
-        // tile j has landed (this wave's share), then everybody's share; the barrier also says that
-        // every wave is done reading tile j-1, whose stage the next copy overwrites
-        if (j + 1 < nt) wait_vmcnt<2 * CPW>(); else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
-        if (j + 2 < nt) {
-            int s2 = stage + 2; if (s2 >= STAGES) s2 -= STAGES;
-            issue_tile(j + 2, s2);
-        }
-        const int kv0 = j * BN;
-        const char* sk = smem + stage * STAGE_BYTES + k_lane;
-        const char* sv = smem + stage * STAGE_BYTES + v_lane;
-        stage = (stage + 1 == STAGES) ? 0 : stage + 1;
+    // K fragment (A operand of T): keys kb*32 + lane%32, features (kk*2 + lane/32)*8 .. +7
+    auto read_kf = [&](const char* sk, int kb, int kk) -> s16x8 {
+        return *reinterpret_cast<const s16x8*>(sk + ((kk >> 1) * RB + kb * 2) * 1024 + (kk & 1) * 512);
+    };
+    // V^T fragment (A operand of U): features db*32 + lane%32, the 8 keys of half kb that the P
+    // operand of MFMA ks holds in this lane group, fetched with the transposing LDS read
+    auto read_vf = [&](const char* sv, int kb, int ks, int db) -> s16x8 {
+        const char* a = sv + db * (BN * 64) + (kb * 32 + ks * 16) * 64;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(a));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(a + 8 * 64));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
 
-        if (CAUSAL && kv0 > wq0 + MB * 32 - 1) continue;   // every key of the tile is hidden from this wave
-
-        // ---- T: S^T = K Q^T
-        f32x16 S[MB][KB];
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                const s16x8 kf = *reinterpret_cast<const s16x8*>(sk + ((kk >> 1) * RB + kb * 2) * 1024 + (kk & 1) * 512);
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    if (kk == 0) {
-                        f32x16 z;
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) z[i] = 0.f;
-                        S[mb][kb] = E::mfma(kf, Qf[mb][kk], z);
-                    } else {
-                        S[mb][kb] = E::mfma(kf, Qf[mb][kk], S[mb][kb]);
-                    }
-                }
-            }
-        }
-
-        // ---- mask: keys past the end of the sequence, and keys after the query when causal
-        const bool need_mask = (kv0 + BN > N) || (CAUSAL && kv0 + BN - 1 > wq0);
-        if (need_mask) {
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const int qi = wq0 + mb * 32 + lr;
-                const int lim = CAUSAL ? min(qi, N - 1) : N - 1;   // last visible key
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int key = kv0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-                        if (key > lim) S[mb][kb][i] = -__builtin_inff();
-                    }
-            }
-        }
-
-        // ---- C: streaming softmax (base-2 exponentials, scale folded into the exponent)
-        s16x8 Pf[MB][KB][2];
+    // mask of one half's scores: keys past the end of the sequence, and keys after the query when causal
+    auto mask_half = [&](f32x16 (&S)[MB], int key0) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            float mx = S[mb][0][0];
+            const int qi = wq0 + mb * 32 + lr;
+            const int lim = CAUSAL ? min(qi, N - 1) : N - 1;   // last visible key
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = __builtin_fmaxf(mx, S[mb][kb][i]);
-            mx = xor32_max(mx);
-            const float m_new = __builtin_fmaxf(m_run[mb], mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_run[mb] - m_new) * scale_log2e);
-            const float neg_mc = -m_new * scale_log2e;
-            m_run[mb] = m_new;
-            float sum = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                float p[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][kb][i], scale_log2e, neg_mc));
-                    sum += p[i];
-                }
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    u32x4 w;
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) w[t] = E::pack2(p[ks * 8 + 2 * t], p[ks * 8 + 2 * t + 1]);
-                    Pf[mb][kb][ks] = __builtin_bit_cast(s16x8, w);
-                }
+            for (int i = 0; i < 16; ++i) {
+                const int key = key0 + (i >> 2) * 8 + g * 4 + (i & 3);
+                if (key > lim) S[mb][i] = -__builtin_inff();
             }
-            l_run[mb] = l_run[mb] * alpha + sum;
+        }
+    };
+    auto half_needs_mask = [&](int h) -> bool {
+        const int key_last = h * 32 + 31;
+        return key_last > N - 1 || (CAUSAL && key_last > wq0);
+    };
+
+    // First part of C for one half: from its row maxima `mx`, the new softmax reference.  The running
+    // reference m only moves when a row maximum grew by more than 2^RESCALE_LOG2 (the probabilities
+    // then stay below that factor), so the rescaling of O is rare after the first tiles.
+    auto new_reference = [&](const float (&mx)[MB]) {
+        bool upd_any = false;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+        for (int mb = 0; mb < MB; ++mb) {
+            const float mxa = xor32_max(mx[mb]);
+            const float m_old = m_run[mb];
+            const float m_new = __builtin_fmaxf(m_old, mxa);
+            const bool upd = (m_new - m_old) * scale_log2e > RESCALE_LOG2;
+            const float m_use = upd ? m_new : m_old;
+            upd_any |= upd;
+            alpha[mb] = __builtin_amdgcn_exp2f((m_old - m_use) * scale_log2e);
+            neg_mc[mb] = -m_use * scale_log2e;
+            m_run[mb] = m_use;
+        }
+        any_upd = __builtin_amdgcn_ballot_w64(upd_any) != 0;
+    };
+
+    // ---- one step of the coarse-grained pipeline (Algorithm 1 of the paper, in its dependency-correct
+    // order) on a 32-key half h of the sequence.  On entry S holds the half's masked scores and
+    // new_reference() has been run on them.
+    //   matrix cores: T_{h+1} = K_{h+1} Q^T                then U_h = V_h^T P_h^T
+    //   vector ALU:   exponentials, row sums, P of half h   then row maxima / reference of half h+1
+    // The two streams are interleaved by hand, one MFMA per chunk of vector work, and a scheduling
+    // barrier after every chunk keeps the compiler from regrouping them: an MFMA executes for 32
+    // cycles after it is issued and the vector instructions behind it run in its shadow.
+    // sk: K tile holding half h+1 (+ k_lane), sv: V tile holding half h (+ v_lane).
+    auto half_step = [&](auto maskn_c, auto next_c, f32x16 (&S)[MB], f32x16 (&Sn)[MB], int h, const char* sk, const char* sv) {
+        constexpr bool MASKN = decltype(maskn_c)::value;
+        constexpr bool NEXT = decltype(next_c)::value;
+        constexpr int KWIN = ATTN_KWIN < KK ? ATTN_KWIN : KK;          // K fragments requested ahead of their MFMA
+        constexpr int NVF = 2 * DB;                                    // V^T fragments (= MFMAs of U per query block)
+        constexpr int VWIN = ATTN_VWIN < NVF ? ATTN_VWIN : NVF;        // V^T fragments requested ahead
+        constexpr int EPC = 16 / KK;                                   // scores handled next to each MFMA of T
+        constexpr int MPC = 16 / NVF;                                  // maxima handled next to each MFMA of U
+        static_assert(EPC >= 2 && EPC % 2 == 0 && MPC >= 1 && VWIN <= KK, "chunking of the vector work");
+        const int kbn = (h + 1) & 1, kbc = h & 1;                      // position of the halves inside their tiles
+
+        if (any_upd) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) O[mb][db][i] *= alpha;
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) O[mb][db][i] *= alpha[mb];
         }
 
-        // ---- U: O^T += V^T P^T
+        // ---- phase 1: T_{h+1} under the exponentials of half h
+        s16x8 kf[KK], vf[NVF];
+        unsigned pw[MB][8];
+        float sum[MB];
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
+        for (int mb = 0; mb < MB; ++mb) sum[mb] = 0.f;
+        if (NEXT) {
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
+            for (int i = 0; i < KWIN; ++i) kf[i] = read_kf(sk, kbn, i);
+        }
 #pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const char* a = sv + db * (BN * 64) + (kb * 32 + ks * 16) * 64;
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(a));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(a + 8 * 64));
-                    const s16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        for (int i = 0; i < KK; ++i) {
+            if (NEXT) {
+                if (i + KWIN < KK) kf[i + KWIN] = read_kf(sk, kbn, i + KWIN);
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) O[mb][db] = E::mfma(vf, Pf[mb][kb][ks], O[mb][db]);
+                for (int mb = 0; mb < MB; ++mb) {
+                    if (i == 0) {
+                        f32x16 z;
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) z[e] = 0.f;
+                        Sn[mb] = E::mfma(kf[i], Qf[mb][i], z);
+                    } else {
+                        Sn[mb] = E::mfma(kf[i], Qf[mb][i], Sn[mb]);
+                    }
                 }
+            }
+            if (i + VWIN >= KK) {                               // the first V^T fragments, late in the phase
+                const int f = i + VWIN - KK;
+                vf[f] = read_vf(sv, kbc, f / DB, f % DB);
+            }
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                float pe[EPC];
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) {
+                    pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][EPC * i + e], scale_log2e, neg_mc[mb]));
+                    sum[mb] += pe[e];
+                }
+#pragma unroll
+                for (int e = 0; e < EPC; e += 2) pw[mb][(EPC * i + e) / 2] = E::pack2(pe[e], pe[e + 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) l_run[mb] = l_run[mb] * alpha[mb] + sum[mb];
+
+        // ---- phase 2: U_h under the row maxima of half h+1
+        if (NEXT && MASKN) mask_half(Sn, (h + 1) * 32);
+        float mx[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) mx[mb] = -__builtin_inff();
+#pragma unroll
+        for (int f = 0; f < NVF; ++f) {
+            if (f + VWIN < NVF) vf[f + VWIN] = read_vf(sv, kbc, (f + VWIN) / DB, (f + VWIN) % DB);
+            const int ks = f / DB, db = f % DB;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                u32x4 w;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) w[t] = pw[mb][ks * 4 + t];
+                O[mb][db] = E::mfma(vf[f], __builtin_bit_cast(s16x8, w), O[mb][db]);
+            }
+            if (NEXT) {
+#pragma unroll
+                for (int e = f * MPC; e < (f + 1) * MPC; ++e)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) mx[mb] = __builtin_fmaxf(mx[mb], Sn[mb][e]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (NEXT) new_reference(mx);
+    };
+
+    auto run_half = [&](f32x16 (&S)[MB], f32x16 (&Sn)[MB], int h, const char* sk, const char* sv) {
+        if (h >= nh_w) return;
+        if (h + 1 < nh_w) {
+            if (half_needs_mask(h + 1)) half_step(std::true_type{}, std::true_type{}, S, Sn, h, sk, sv);
+            else half_step(std::false_type{}, std::true_type{}, S, Sn, h, sk, sv);
+        } else {
+            half_step(std::false_type{}, std::false_type{}, S, Sn, h, sk, sv);
+        }
+    };
+
+    // ---- T_0 and its reference, not overlapped with anything
+    f32x16 Sa[MB], Sb[MB];
+    __builtin_amdgcn_s_barrier();      // every wave's share of tile 0 is in the LDS
+    {
+        const char* sk = smem + k_lane;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const s16x8 kf = read_kf(sk, 0, kk);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                if (kk == 0) {
+                    f32x16 z;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) z[e] = 0.f;
+                    Sa[mb] = E::mfma(kf, Qf[mb][kk], z);
+                } else {
+                    Sa[mb] = E::mfma(kf, Qf[mb][kk], Sa[mb]);
+                }
+            }
+        }
+        if (half_needs_mask(0)) mask_half(Sa, 0);
+        float mx[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            mx[mb] = Sa[mb][0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) mx[mb] = __builtin_fmaxf(mx[mb], Sa[mb][e]);
+        }
+        new_reference(mx);
+        any_upd = false;               // O is still zero: nothing to rescale
+    }
+
+    // ---- main loop over the K/V tiles; each tile is two half steps, so Sa/Sb swap roles twice per tile.
+    // sync(j): tile j+1 (read by the second half step) has landed once at most tile j+2's copies are
+    // outstanding; the barrier extends that to every wave's share and tells that tile j-1 is no
+    // longer read, so its stage can take tile j+3.
+    int stage = 0;
+    auto sync_and_prefetch = [&](int j) {
+        if (j + 2 < nt) wait_vmcnt<2 * CPW>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (j + 3 < nt) issue_tile(j + 3, (stage + 3) % STAGES);
+    };
+
+    // Halves before `h_plain_end` need no mask and have a successor: their tiles run the branch-free
+    // body.  The few tiles after that (sequence tail, causal diagonal, idle tail of a causal wave) go
+    // through the general path with its run-time case distinctions.
+    int h_plain_end = min(nh_w, N / 32);
+    if (CAUSAL) h_plain_end = min(h_plain_end, wq0 / 32);
+    const int n_plain = h_plain_end > 0 ? (h_plain_end - 1) / 2 : 0;   // tiles j with 2j+2 < h_plain_end
+
+    int j = 0;
+    for (; j < n_plain; ++j) {
+        sync_and_prefetch(j);
+        const int stage_n = (stage + 1) % STAGES;
+        const char* s_cur = smem + stage * STAGE_BYTES;
+        const char* s_nxt = smem + stage_n * STAGE_BYTES;
+        half_step(std::false_type{}, std::true_type{}, Sa, Sb, 2 * j, s_cur + k_lane, s_cur + v_lane);
+        half_step(std::false_type{}, std::true_type{}, Sb, Sa, 2 * j + 1, s_nxt + k_lane, s_cur + v_lane);
+        stage = stage_n;
+    }
+    for (; j < nt; ++j) {
+        sync_and_prefetch(j);
+        const int stage_n = (stage + 1) % STAGES;
+        const char* s_cur = smem + stage * STAGE_BYTES;
+        const char* s_nxt = smem + stage_n * STAGE_BYTES;
+        run_half(Sa, Sb, 2 * j, s_cur + k_lane, s_cur + v_lane);          // T of this tile's second half, U of its first
+        run_half(Sb, Sa, 2 * j + 1, s_nxt + k_lane, s_cur + v_lane);      // T of the next tile's first half, U of this tile's second
+        stage = stage_n;
     }
 
     // ---- epilogue: normalise, write O (16-bit) and LSE (natural log)

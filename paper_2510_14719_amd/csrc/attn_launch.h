@@ -12,7 +12,7 @@
 #define ATTN_CFG_BN 64       // keys per K/V tile
 #endif
 #ifndef ATTN_CFG_STAGES
-#define ATTN_CFG_STAGES 3    // LDS ring depth
+#define ATTN_CFG_STAGES 4    // LDS ring depth
 #endif
 
 struct AttnLaunchArgs {
