@@ -2,18 +2,29 @@
 // per-row log-sum-exp, in one kernel with a streaming softmax.
 //
 // The three stages of one key/value tile follow the paper's Section 3.4.2: T = Q K^T on the matrix
-// cores, C = softmax on the vector ALU, U = P V on the matrix cores.  The paper's Hopper design
-// (a producer warp feeding consumer warp groups through asynchronous references, Section 3.2-3.3)
-// is replaced by what gfx950 offers: every wave of a workgroup issues its share of the global -> LDS
-// copies of the K/V tile two tiles ahead (direct-to-LDS loads, no register staging), the LDS holds a
-// ring of STAGES tiles (the counterpart of an aref ring of depth D, Section 3.3.2), and one
-// s_waitcnt + s_barrier per tile plays the role of the full/empty credits: a stage is overwritten
-// only after every wave has passed the barrier that follows its last read of it.
+// cores, C = softmax on the vector ALU, U = P V on the matrix cores, and the goal is the one of its
+// coarse-grained pipeline (Algorithm 1): keep the matrix cores busy while the vector ALU works.
+//
+// What carries over from the paper's Hopper design and what does not:
+//  * Producer/consumer warp roles are gone.  Every wave issues its share of the global -> LDS copies
+//    (direct-to-LDS loads, no register staging) two tiles ahead of their use.  The LDS holds a ring of
+//    STAGES tiles, the counterpart of an aref ring of depth D (Section 3.3.2); one s_waitcnt plus one
+//    s_barrier per tile play the role of the full/empty credits: a stage is overwritten only after
+//    every wave has passed the barrier that follows its last read of it.
+//  * A gfx950 wave issues in order and cannot run its own vector instructions under its own MFMA
+//    (measured: one wave alternating 1 MFMA + n FMAs takes 41 + 4n cycles per pair), so the overlap of
+//    Algorithm 1 cannot live inside one instruction stream.  It is realised BETWEEN the two waves that
+//    share a SIMD: the eight waves of a workgroup form two groups of four (one wave of each group per
+//    SIMD) that run the same pipeline half a period apart,
+//        group A after barrier j:  [U_{j-1}, T_j] on the matrix cores, then C_j on the vector ALU
+//        group B after barrier j:  C_j on the vector ALU, then [U_j, T_{j+1}] on the matrix cores
+//    so while one wave of a SIMD streams 32 MFMAs the other one does its softmax.  The workgroup
+//    barrier re-locks the two groups into opposite phases every tile.
 //
 // Register layout.  The scores are computed transposed, S^T = K Q^T, with the 32x32x16 MFMA: the
 // K tile is the A operand (32 keys x 16 features), Q^T the B operand.  A lane then owns ONE query
 // (column lane%32 of the result) and 16 of the 32 keys of a block; the other 16 keys of that query
-// sit in lane^32.  Row maximum and row sum are 15 in-lane operations plus one lane<->lane+32
+// sit in lane^32.  Row maximum and row sum are in-lane operations plus one lane<->lane+32
 // exchange, and the probabilities are already laid out as the B operand of the second contraction
 // O^T = V^T P^T.  V^T fragments come from the LDS through the transposing 64-bit read of gfx950.
 
@@ -38,12 +49,9 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 // The softmax reference moves only when a row maximum grew by more than this many powers of two.
 constexpr float RESCALE_LOG2 = 8.0f;
 
-// Tuning knobs of the hand-interleaved pipeline (see tile_step).
-#ifndef ATTN_KWIN
-#define ATTN_KWIN 3
-#endif
-#ifndef ATTN_VWIN
-#define ATTN_VWIN 3
+// LDS fragments requested ahead of their MFMA inside a burst (see mfma_burst).
+#ifndef ATTN_FWIN
+#define ATTN_FWIN 4
 #endif
 
 // Element-type traits: MFMA flavour and fp32 -> 16-bit conversion (round to nearest even).
@@ -58,6 +66,11 @@ template <> struct Elem<0> {  // IEEE binary16
         f32x2 x = {lo, hi};
         return __builtin_bit_cast(unsigned, __builtin_convertvector(x, v2));
     }
+    // acc + lo + hi of a packed pair (the rounded values, as the second contraction sees them)
+    static __device__ __forceinline__ float add_pair(unsigned w, float acc) {
+        const v2 one = {(_Float16)1.0f, (_Float16)1.0f};
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(v2, w), one, acc, false);
+    }
 };
 template <> struct Elem<1> {  // bfloat16
     typedef __bf16 v8 __attribute__((ext_vector_type(8)));
@@ -68,6 +81,10 @@ template <> struct Elem<1> {  // bfloat16
     static __device__ __forceinline__ unsigned pack2(float lo, float hi) {
         f32x2 x = {lo, hi};
         return __builtin_bit_cast(unsigned, __builtin_convertvector(x, v2));
+    }
+    static __device__ __forceinline__ float add_pair(unsigned w, float acc) {
+        const v2 one = {(__bf16)1.0f, (__bf16)1.0f};
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2, w), one, acc, false);
     }
 };
 
@@ -82,6 +99,22 @@ __device__ __forceinline__ void dma16(const void* gbase, unsigned voff, unsigned
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
+
+#ifdef ATTN_TIMING
+// Profiling builds only: per-wave cycle totals of the main-loop sections of the first workgroups.
+constexpr int DBG_WGS = 1024, DBG_SLOTS = 8;
+__device__ unsigned long long attn_dbg[DBG_WGS * 8 * DBG_SLOTS];
+#if ATTN_TIMING >= 2
+#define TSTAMP(var) const unsigned long long var = __builtin_readcyclecounter()
+#define TACC(slot, a, b) dbg_acc[slot] += (b) - (a)
+#else
+#define TSTAMP(var)
+#define TACC(slot, a, b)
+#endif
+#else
+#define TSTAMP(var)
+#define TACC(slot, a, b)
+#endif
 
 // Exchange with lane^32 (v_permlane32_swap swaps the upper 32 lanes of its first operand with the
 // lower 32 lanes of its second): afterwards `a` holds the lower half's values on every lane and `b`
@@ -120,7 +153,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 {
     typedef Elem<DTYPE> E;
     constexpr int BM = NW * MB * 32;            // query rows per workgroup
-    constexpr int KB = BN / 32;                 // 32-key blocks ("halves") per K/V tile
+    constexpr int KB = BN / 32;                 // 32-key blocks per K/V tile
     constexpr int KK = D / 16;                  // contraction steps of Q K^T
     constexpr int DB = D / 32;                  // 32-wide feature blocks of O
     constexpr int ROW_BYTES = D * 2;
@@ -129,16 +162,21 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int RB = BN / 16;                 // 16-row blocks per tile
     constexpr int CHUNKS = TILE_BYTES / 1024;   // 1 KiB wave-transfers per tile
     constexpr int CPW = CHUNKS / NW;            // ... per wave
+    constexpr int LPG = 2 * CPW;                // copies a wave issues per stage (K part + V part)
     static_assert(CHUNKS % NW == 0, "tile must split evenly over the waves");
-    static_assert(STAGES == 4, "the ring protocol below keeps tiles j..j+3 in four stages");
-    static_assert(KB == 2, "a tile is processed as two 32-key halves");
+    static_assert(STAGES == 4, "the ring protocol below keeps four stages");
+    static_assert(NW == 8, "two groups of four waves, one wave of each group per SIMD");
 
+#ifdef ATTN_TIMING
+    const unsigned long long rt_kernel_entry = __builtin_amdgcn_s_memrealtime();
+#endif
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const unsigned lds_base = (unsigned)(size_t)(LDS_AS void*)smem;
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in an SGPR
     const int lane = threadIdx.x & 63;
     const int lr = lane & 31, g = lane >> 5;
+    const bool group_b = wave >= NW / 2;        // waves w and w + 4 share a SIMD
 
     // ---- which (batch*head, query tile) this workgroup owns
     const int logical = xcd_remap(blockIdx.x, total);
@@ -153,59 +191,61 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     const char* kh = reinterpret_cast<const char*>(k + head_off);
     const char* vh = reinterpret_cast<const char*>(v + head_off);
 
-    // ---- number of K/V tiles the workgroup walks, and of 32-key halves this wave computes on
+    // ---- number of K/V tiles the workgroup walks, and the number this wave computes on
     int nt = (N + BN - 1) / BN;
     if (CAUSAL) {
         const int last_q = min(q0 + BM, N) - 1;
         nt = min(nt, last_q / BN + 1);
     }
-    int nh_w = min(2 * nt, (N + 31) / 32);                              // halves that hold a real key
-    if (CAUSAL) nh_w = min(nh_w, (wq0 + MB * 32 - 1) / 32 + 1);         // ... and one this wave's rows can see
+    int nt_w = nt;
+    if (CAUSAL) nt_w = min(nt, (wq0 + MB * 32 - 1) / BN + 1);   // later tiles are wholly hidden from this wave's rows
 
-    // ---- global -> LDS copies.  A wave moves CPW 1 KiB pieces of K and of V per tile.
+    // ---- global -> LDS copies.  Stage s of the ring holds K tile s+1 and V tile s: the pair that one
+    // MFMA burst reads (U_s needs V_s, T_{s+1} needs K_{s+1}).  A wave moves CPW 1 KiB pieces of each.
     // K tile in LDS: [feature group of 32][16-row block][16-byte column of the group (4)][row (16)][16 B]
     // V tile in LDS: [feature group of 32][row (BN)][64 B]
     // Lane L of a K piece fetches row L%16, column L/16 of the piece's (16 rows x 64 B) source block; of
     // a V piece row L/4, column L%4.  Inside the sequence the per-lane offset is a constant and the
-    // tile/piece offset is added to the scalar base; the clamped form serves the tile that overruns N.
+    // tile/piece offset is added to the scalar base; the clamped form serves tiles that overrun the
+    // sequence (their surplus rows are masked or never read).
     const unsigned k_lane_off = (lane & 15) * ROW_BYTES + (lane >> 4) * 16;
     const unsigned v_lane_off = (lane >> 2) * ROW_BYTES + (lane & 3) * 16;
-    auto issue_tile = [&](int t, int stage) {
-        const int kv0 = t * BN;
-        const unsigned sbase = lds_base + stage * STAGE_BYTES;
-        if (kv0 + BN <= N) {
+    int piece_src[CPW], piece_dst[CPW];         // wave-uniform: source offset inside a tile, LDS offset inside a K or V slot
 #pragma unroll
-            for (int i = 0; i < CPW; ++i) {
-                const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
-                const size_t off = (size_t)(kv0 + rb * 16) * ROW_BYTES + fg * 64;
-                dma16(kh + off, k_lane_off, sbase + wc * 1024);
-            }
+    for (int i = 0; i < CPW; ++i) {
+        const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
+        piece_src[i] = rb * 16 * ROW_BYTES + fg * 64;
+        piece_dst[i] = wc * 1024;
+    }
+    auto issue_stage = [&](int s) __attribute__((always_inline)) {             // s = -1 is the stage that only brings K tile 0
+        const unsigned sbase = lds_base + ((s + STAGES) % STAGES) * STAGE_BYTES;
+        if (s >= 0 && (s + 2) * BN <= N) {      // K tile s+1 and V tile s lie wholly inside the sequence
+            const char* kt = kh + (size_t)(s + 1) * TILE_BYTES;
+            const char* vt = vh + (size_t)s * TILE_BYTES;
 #pragma unroll
-            for (int i = 0; i < CPW; ++i) {
-                const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
-                const size_t off = (size_t)(kv0 + rb * 16) * ROW_BYTES + fg * 64;
-                dma16(vh + off, v_lane_off, sbase + TILE_BYTES + wc * 1024);
-            }
+            for (int i = 0; i < CPW; ++i) dma16(kt + piece_src[i], k_lane_off, sbase + piece_dst[i]);
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) dma16(vt + piece_src[i], v_lane_off, sbase + TILE_BYTES + piece_dst[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < CPW; ++i) {
                 const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
-                const int row = min(kv0 + rb * 16 + (lane & 15), N - 1);
-                dma16(kh, (unsigned)(row * ROW_BYTES + fg * 64 + (lane >> 4) * 16), sbase + wc * 1024);
+                const int row = min(max((s + 1) * BN + rb * 16 + (lane & 15), 0), N - 1);
+                dma16(kh, (unsigned)(row * ROW_BYTES + fg * 64 + (lane >> 4) * 16), sbase + piece_dst[i]);
             }
 #pragma unroll
             for (int i = 0; i < CPW; ++i) {
                 const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
-                const int row = min(kv0 + rb * 16 + (lane >> 2), N - 1);
-                dma16(vh, (unsigned)(row * ROW_BYTES + fg * 64 + (lane & 3) * 16), sbase + TILE_BYTES + wc * 1024);
+                const int row = min(max(s * BN + rb * 16 + (lane >> 2), 0), N - 1);
+                dma16(vh, (unsigned)(row * ROW_BYTES + fg * 64 + (lane & 3) * 16), sbase + TILE_BYTES + piece_dst[i]);
             }
         }
     };
 
-    // ---- prologue: up to three tiles in flight, Q fragments into registers
-    issue_tile(0, 0);
-    if (nt > 1) issue_tile(1, 1);
-    if (nt > 2) issue_tile(2, 2);
+    // ---- prologue: three stages in flight, Q fragments into registers
+    issue_stage(-1);
+    issue_stage(0);
+    issue_stage(1);
 
     s16x8 Qf[MB][KK];
 #pragma unroll
@@ -218,263 +258,153 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     }
     // Use the Q fragments once here: the compiler then waits for their loads before the loop instead
     // of inside it, where its vmcnt(0) would also wait for the K/V copies issued a moment earlier.
-    // (The Q loads were issued after the tile copies, so this wait also covers tiles 0..2.)
+    // (The Q loads were issued after the copies above, so this wait also covers stages -1, 0 and 1.)
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) asm volatile("" :: "v"(Qf[mb][kk]));
 
-    f32x16 O[MB][DB];
-    float m_run[MB], l_run[MB], alpha[MB], neg_mc[MB];
+    f32x16 O[MB][DB], S[MB][KB];
+    unsigned pw[MB][KB * 8];                    // P of the current tile as packed 16-bit pairs
+    float m_run[MB], l_run[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         m_run[mb] = -__builtin_inff();
         l_run[mb] = 0.f;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) O[mb][db][i] = 0.f;
+        for (int db = 0; db < DB; ++db) O[mb][db] = f32x16(0.f);
     }
-    bool any_upd = false;
 
     // per-lane LDS read offsets (the rest of every address is an immediate)
     const int k_lane = (lr >> 4) * 1024 + g * 256 + (lr & 15) * 16;
     const int v_lane = TILE_BYTES + (4 * g + ((lane & 15) >> 2)) * 64 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
 
     // K fragment (A operand of T): keys kb*32 + lane%32, features (kk*2 + lane/32)*8 .. +7
-    auto read_kf = [&](const char* sk, int kb, int kk) -> s16x8 {
+    auto read_kf = [&](const char* sk, int kb, int kk) __attribute__((always_inline)) -> s16x8 {
         return *reinterpret_cast<const s16x8*>(sk + ((kk >> 1) * RB + kb * 2) * 1024 + (kk & 1) * 512);
     };
-    // V^T fragment (A operand of U): features db*32 + lane%32, the 8 keys of half kb that the P
+    // V^T fragment (A operand of U): features db*32 + lane%32, the 8 keys of block kb that the P
     // operand of MFMA ks holds in this lane group, fetched with the transposing LDS read
-    auto read_vf = [&](const char* sv, int kb, int ks, int db) -> s16x8 {
+    auto read_vf = [&](const char* sv, int kb, int ks, int db) __attribute__((always_inline)) -> s16x8 {
         const char* a = sv + db * (BN * 64) + (kb * 32 + ks * 16) * 64;
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(a));
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(a + 8 * 64));
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
-    // mask of one half's scores: keys past the end of the sequence, and keys after the query when causal
-    auto mask_half = [&](f32x16 (&S)[MB], int key0) {
+    // ---- MFMA burst on one stage: U (O^T += V^T P^T with the P in pw) and/or T (S^T = K Q^T), as one
+    // stream of MFMAs whose LDS fragments are requested FWIN MFMAs ahead.  The scheduling barriers
+    // keep that order: left alone the compiler requests each fragment right before its MFMA.
+    auto mfma_burst = [&](auto do_u, auto do_t, const char* stage_ptr) __attribute__((always_inline)) {
+        constexpr int NU = decltype(do_u)::value ? KB * 2 * DB : 0;
+        constexpr int NT = decltype(do_t)::value ? KB * KK : 0;
+        constexpr int NF = NU + NT;
+        constexpr int FWIN = ATTN_FWIN < NF ? ATTN_FWIN : NF;
+        const char* sk = stage_ptr + k_lane;
+        const char* sv = stage_ptr + v_lane;
+        s16x8 fr[NF];
+        auto fetch = [&](int f) __attribute__((always_inline)) {
+            if (f < NU) fr[f] = read_vf(sv, f / (2 * DB), (f / DB) % 2, f % DB);
+            else fr[f] = read_kf(sk, (f - NU) % KB, (f - NU) / KB);
+        };
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int qi = wq0 + mb * 32 + lr;
-            const int lim = CAUSAL ? min(qi, N - 1) : N - 1;   // last visible key
+        for (int f = 0; f < FWIN; ++f) fetch(f);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int key = key0 + (i >> 2) * 8 + g * 4 + (i & 3);
-                if (key > lim) S[mb][i] = -__builtin_inff();
+        for (int f = 0; f < NF; ++f) {
+            if (f + FWIN < NF) fetch(f + FWIN);
+            if (f < NU) {
+                const int kb = f / (2 * DB), ks = (f / DB) % 2, db = f % DB;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    u32x4 w;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) w[t] = pw[mb][kb * 8 + ks * 4 + t];
+                    O[mb][db] = E::mfma(fr[f], __builtin_bit_cast(s16x8, w), O[mb][db]);
+                }
+            } else {
+                const int kb = (f - NU) % KB, kk = (f - NU) / KB;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    S[mb][kb] = E::mfma(fr[f], Qf[mb][kk], kk == 0 ? f32x16(0.f) : S[mb][kb]);
+                }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
-    auto half_needs_mask = [&](int h) -> bool {
-        const int key_last = h * 32 + 31;
-        return key_last > N - 1 || (CAUSAL && key_last > wq0);
-    };
 
-    // First part of C for one half: from its row maxima `mx`, the new softmax reference.  The running
-    // reference m only moves when a row maximum grew by more than 2^RESCALE_LOG2 (the probabilities
-    // then stay below that factor), so the rescaling of O is rare after the first tiles.
-    auto new_reference = [&](const float (&mx)[MB]) {
+    // ---- C of tile j: mask, streaming softmax of S into pw, running maximum / sum, rescaling of O.
+    // Base-2 exponentials with the scale folded into the exponent.  The running reference m only
+    // moves when a row maximum grew by more than 2^RESCALE_LOG2 (the probabilities then stay below
+    // that factor), so the rescaling of O is rare after the first tiles.
+    auto softmax_tile = [&](int j) __attribute__((always_inline)) {
+        const int kv0 = j * BN;
+        if ((kv0 + BN > N) || (CAUSAL && kv0 + BN - 1 > wq0)) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const int qi = wq0 + mb * 32 + lr;
+                const int lim = CAUSAL ? min(qi, N - 1) : N - 1;   // last visible key
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = kv0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
+                        if (key > lim) S[mb][kb][i] = -__builtin_inff();
+                    }
+            }
+        }
+        float alpha[MB];
         bool upd_any = false;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const float mxa = xor32_max(mx[mb]);
+            float mx = S[mb][0][0];
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = __builtin_fmaxf(mx, S[mb][kb][i]);
+            mx = xor32_max(mx);
             const float m_old = m_run[mb];
-            const float m_new = __builtin_fmaxf(m_old, mxa);
+            const float m_new = __builtin_fmaxf(m_old, mx);
             const bool upd = (m_new - m_old) * scale_log2e > RESCALE_LOG2;
             const float m_use = upd ? m_new : m_old;
             upd_any |= upd;
             alpha[mb] = __builtin_amdgcn_exp2f((m_old - m_use) * scale_log2e);
-            neg_mc[mb] = -m_use * scale_log2e;
+            const float neg_mc = -m_use * scale_log2e;
             m_run[mb] = m_use;
+            float sum0 = 0.f, sum1 = 0.f;       // two chains: the pair sums do not wait for each other
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][kb][2 * t], scale_log2e, neg_mc));
+                    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][kb][2 * t + 1], scale_log2e, neg_mc));
+                    const unsigned w = E::pack2(p0, p1);
+                    pw[mb][kb * 8 + t] = w;
+                    if (t & 1) sum1 = E::add_pair(w, sum1); else sum0 = E::add_pair(w, sum0);
+                }
+            l_run[mb] = l_run[mb] * alpha[mb] + (sum0 + sum1);
         }
-        any_upd = __builtin_amdgcn_ballot_w64(upd_any) != 0;
-    };
-
-    // ---- one step of the coarse-grained pipeline (Algorithm 1 of the paper, in its dependency-correct
-    // order) on a 32-key half h of the sequence.  On entry S holds the half's masked scores and
-    // new_reference() has been run on them.
-    //   matrix cores: T_{h+1} = K_{h+1} Q^T                then U_h = V_h^T P_h^T
-    //   vector ALU:   exponentials, row sums, P of half h   then row maxima / reference of half h+1
-    // The two streams are interleaved by hand, one MFMA per chunk of vector work, and a scheduling
-    // barrier after every chunk keeps the compiler from regrouping them: an MFMA executes for 32
-    // cycles after it is issued and the vector instructions behind it run in its shadow.
-    // sk: K tile holding half h+1 (+ k_lane), sv: V tile holding half h (+ v_lane).
-    auto half_step = [&](auto maskn_c, auto next_c, f32x16 (&S)[MB], f32x16 (&Sn)[MB], int h, const char* sk, const char* sv) {
-        constexpr bool MASKN = decltype(maskn_c)::value;
-        constexpr bool NEXT = decltype(next_c)::value;
-        constexpr int KWIN = ATTN_KWIN < KK ? ATTN_KWIN : KK;          // K fragments requested ahead of their MFMA
-        constexpr int NVF = 2 * DB;                                    // V^T fragments (= MFMAs of U per query block)
-        constexpr int VWIN = ATTN_VWIN < NVF ? ATTN_VWIN : NVF;        // V^T fragments requested ahead
-        constexpr int EPC = 16 / KK;                                   // scores handled next to each MFMA of T
-        constexpr int MPC = 16 / NVF;                                  // maxima handled next to each MFMA of U
-        static_assert(EPC >= 2 && EPC % 2 == 0 && MPC >= 1 && VWIN <= KK, "chunking of the vector work");
-        const int kbn = (h + 1) & 1, kbc = h & 1;                      // position of the halves inside their tiles
-
-        if (any_upd) {
+        if (__builtin_amdgcn_ballot_w64(upd_any) != 0) {
+            // whole-vector multiplies: element-wise updates would make the compiler split the
+            // accumulator tuples into scalars and re-assemble them around every MFMA
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) O[mb][db][i] *= alpha[mb];
-        }
-
-        // ---- phase 1: T_{h+1} under the exponentials of half h
-        s16x8 kf[KK], vf[NVF];
-        unsigned pw[MB][8];
-        float sum[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) sum[mb] = 0.f;
-        if (NEXT) {
-#pragma unroll
-            for (int i = 0; i < KWIN; ++i) kf[i] = read_kf(sk, kbn, i);
-        }
-#pragma unroll
-        for (int i = 0; i < KK; ++i) {
-            if (NEXT) {
-                if (i + KWIN < KK) kf[i + KWIN] = read_kf(sk, kbn, i + KWIN);
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    if (i == 0) {
-                        f32x16 z;
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) z[e] = 0.f;
-                        Sn[mb] = E::mfma(kf[i], Qf[mb][i], z);
-                    } else {
-                        Sn[mb] = E::mfma(kf[i], Qf[mb][i], Sn[mb]);
-                    }
-                }
-            }
-            if (i + VWIN >= KK) {                               // the first V^T fragments, late in the phase
-                const int f = i + VWIN - KK;
-                vf[f] = read_vf(sv, kbc, f / DB, f % DB);
-            }
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                float pe[EPC];
-#pragma unroll
-                for (int e = 0; e < EPC; ++e) {
-                    pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][EPC * i + e], scale_log2e, neg_mc[mb]));
-                    sum[mb] += pe[e];
-                }
-#pragma unroll
-                for (int e = 0; e < EPC; e += 2) pw[mb][(EPC * i + e) / 2] = E::pack2(pe[e], pe[e + 1]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) l_run[mb] = l_run[mb] * alpha[mb] + sum[mb];
-
-        // ---- phase 2: U_h under the row maxima of half h+1
-        if (NEXT && MASKN) mask_half(Sn, (h + 1) * 32);
-        float mx[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) mx[mb] = -__builtin_inff();
-#pragma unroll
-        for (int f = 0; f < NVF; ++f) {
-            if (f + VWIN < NVF) vf[f + VWIN] = read_vf(sv, kbc, (f + VWIN) / DB, (f + VWIN) % DB);
-            const int ks = f / DB, db = f % DB;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                u32x4 w;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) w[t] = pw[mb][ks * 4 + t];
-                O[mb][db] = E::mfma(vf[f], __builtin_bit_cast(s16x8, w), O[mb][db]);
-            }
-            if (NEXT) {
-#pragma unroll
-                for (int e = f * MPC; e < (f + 1) * MPC; ++e)
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) mx[mb] = __builtin_fmaxf(mx[mb], Sn[mb][e]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (NEXT) new_reference(mx);
-    };
-
-    auto run_half = [&](f32x16 (&S)[MB], f32x16 (&Sn)[MB], int h, const char* sk, const char* sv) {
-        if (h >= nh_w) return;
-        if (h + 1 < nh_w) {
-            if (half_needs_mask(h + 1)) half_step(std::true_type{}, std::true_type{}, S, Sn, h, sk, sv);
-            else half_step(std::false_type{}, std::true_type{}, S, Sn, h, sk, sv);
-        } else {
-            half_step(std::false_type{}, std::false_type{}, S, Sn, h, sk, sv);
+                for (int db = 0; db < DB; ++db) O[mb][db] = O[mb][db] * alpha[mb];
         }
     };
 
-    // ---- T_0 and its reference, not overlapped with anything
-    f32x16 Sa[MB], Sb[MB];
-    __builtin_amdgcn_s_barrier();      // every wave's share of tile 0 is in the LDS
-    {
-        const char* sk = smem + k_lane;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            const s16x8 kf = read_kf(sk, 0, kk);
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                if (kk == 0) {
-                    f32x16 z;
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) z[e] = 0.f;
-                    Sa[mb] = E::mfma(kf, Qf[mb][kk], z);
-                } else {
-                    Sa[mb] = E::mfma(kf, Qf[mb][kk], Sa[mb]);
-                }
-            }
-        }
-        if (half_needs_mask(0)) mask_half(Sa, 0);
-        float mx[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            mx[mb] = Sa[mb][0];
-#pragma unroll
-            for (int e = 1; e < 16; ++e) mx[mb] = __builtin_fmaxf(mx[mb], Sa[mb][e]);
-        }
-        new_reference(mx);
-        any_upd = false;               // O is still zero: nothing to rescale
-    }
-
-    // ---- main loop over the K/V tiles; each tile is two half steps, so Sa/Sb swap roles twice per tile.
-    // sync(j): tile j+1 (read by the second half step) has landed once at most tile j+2's copies are
-    // outstanding; the barrier extends that to every wave's share and tells that tile j-1 is no
-    // longer read, so its stage can take tile j+3.
-    int stage = 0;
-    auto sync_and_prefetch = [&](int j) {
-        if (j + 2 < nt) wait_vmcnt<2 * CPW>(); else wait_vmcnt<0>();
+    // At barrier j every wave's share of stages <= j has landed (each wave waits for its own copies up
+    // to stage j, leaving only stage j+1's in flight) and nobody reads stage j-2 any more, so that
+    // stage takes the copies of stage j+2.
+    auto wait_stage = [&](int j) __attribute__((always_inline)) {
+        if (j + 1 < nt) wait_vmcnt<LPG>(); else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
-        if (j + 3 < nt) issue_tile(j + 3, (stage + 3) % STAGES);
     };
+    auto stage_ptr = [&](int s) __attribute__((always_inline)) -> const char* { return smem + ((s + STAGES) % STAGES) * STAGE_BYTES; };
 
-    // Halves before `h_plain_end` need no mask and have a successor: their tiles run the branch-free
-    // body.  The few tiles after that (sequence tail, causal diagonal, idle tail of a causal wave) go
-    // through the general path with its run-time case distinctions.
-    int h_plain_end = min(nh_w, N / 32);
-    if (CAUSAL) h_plain_end = min(h_plain_end, wq0 / 32);
-    const int n_plain = h_plain_end > 0 ? (h_plain_end - 1) / 2 : 0;   // tiles j with 2j+2 < h_plain_end
-
-    int j = 0;
-    for (; j < n_plain; ++j) {
-        sync_and_prefetch(j);
-        const int stage_n = (stage + 1) % STAGES;
-        const char* s_cur = smem + stage * STAGE_BYTES;
-        const char* s_nxt = smem + stage_n * STAGE_BYTES;
-        half_step(std::false_type{}, std::true_type{}, Sa, Sb, 2 * j, s_cur + k_lane, s_cur + v_lane);
-        half_step(std::false_type{}, std::true_type{}, Sb, Sa, 2 * j + 1, s_nxt + k_lane, s_cur + v_lane);
-        stage = stage_n;
-    }
-    for (; j < nt; ++j) {
-        sync_and_prefetch(j);
-        const int stage_n = (stage + 1) % STAGES;
-        const char* s_cur = smem + stage * STAGE_BYTES;
-        const char* s_nxt = smem + stage_n * STAGE_BYTES;
-        run_half(Sa, Sb, 2 * j, s_cur + k_lane, s_cur + v_lane);          // T of this tile's second half, U of its first
-        run_half(Sb, Sa, 2 * j + 1, s_nxt + k_lane, s_cur + v_lane);      // T of the next tile's first half, U of this tile's second
-        stage = stage_n;
-    }
-
-    // ---- epilogue: normalise, write O (16-bit) and LSE (natural log)
+    // ---- epilogue: normalise, write O (16-bit) and LSE (natural log).  Expanded at the end of each
+    // group's code path, so that the accumulators of the two paths never have to meet in one register set.
+    auto epilogue = [&]() __attribute__((always_inline)) {
     uint16_t* oh = o + head_off;
     float* lh = lse + (size_t)bh * N;
 #pragma unroll
@@ -496,6 +426,87 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                 }
         }
     }
+    };
+
+    __builtin_amdgcn_s_barrier();               // stages -1, 0, 1 are complete for every wave
+#ifdef ATTN_TIMING
+    unsigned long long dbg_acc[DBG_SLOTS] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime(), ct0 = __builtin_readcyclecounter();
+#endif
+    // Each group's steady state is one loop with a single code path (the first and last tile and the
+    // idle tail of a causal wave are peeled off), so the accumulators stay in place across iterations.
+    if (!group_b) {
+        // group A, iteration j: [U_{j-1}, T_j] then C_j; both contractions read stage j-1
+        wait_stage(0);
+        mfma_burst(std::false_type{}, std::true_type{}, stage_ptr(-1));                  // T_0
+        if (2 < nt) issue_stage(2);
+        softmax_tile(0);
+        auto iter_a = [&](int j) __attribute__((always_inline)) {
+            TSTAMP(t0);
+            wait_stage(j);
+            TSTAMP(t1);
+            mfma_burst(std::true_type{}, std::true_type{}, stage_ptr(j - 1));
+            TSTAMP(t2);
+            if (j + 2 < nt) issue_stage(j + 2);
+            TSTAMP(t3);
+            softmax_tile(j);
+            TSTAMP(t4);
+            TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3); TACC(3, t3, t4);
+        };
+        int j = 1;
+        for (; j < nt_w; ++j) iter_a(j);
+        if (j < nt) wait_stage(j);                                                       // j == nt_w
+        mfma_burst(std::true_type{}, std::false_type{}, stage_ptr(j - 1));               // U of the last tile
+        if (j < nt && j + 2 < nt) issue_stage(j + 2);
+        for (++j; j < nt; ++j) {                                                         // idle tail of a causal wave
+            wait_stage(j);
+            if (j + 2 < nt) issue_stage(j + 2);
+        }
+        epilogue();
+    } else {
+        // group B, iteration j: C_j then [U_j, T_{j+1}]; both contractions read stage j
+        mfma_burst(std::false_type{}, std::true_type{}, stage_ptr(-1));                  // T_0
+        auto iter_b = [&](int j) __attribute__((always_inline)) {
+            TSTAMP(t0);
+            wait_stage(j);
+            TSTAMP(t1);
+            if (j + 2 < nt) issue_stage(j + 2);
+            TSTAMP(t2);
+            softmax_tile(j);
+            TSTAMP(t3);
+            mfma_burst(std::true_type{}, std::true_type{}, stage_ptr(j));
+            TSTAMP(t4);
+            TACC(0, t0, t1); TACC(2, t1, t2); TACC(3, t2, t3); TACC(1, t3, t4);
+        };
+        int j = 0;
+        for (; j + 1 < nt_w; ++j) iter_b(j);
+        wait_stage(j);                                                                   // j == nt_w - 1
+        if (j + 2 < nt) issue_stage(j + 2);
+        softmax_tile(j);
+        mfma_burst(std::true_type{}, std::false_type{}, stage_ptr(j));                   // U of the last tile
+        for (++j; j < nt; ++j) {                                                         // idle tail of a causal wave
+            wait_stage(j);
+            if (j + 2 < nt) issue_stage(j + 2);
+        }
+        epilogue();
+    }
+#ifdef ATTN_TIMING
+    if (blockIdx.x < DBG_WGS && lane == 0) {
+        dbg_acc[5] = nt;
+        dbg_acc[6] = __builtin_amdgcn_s_memrealtime() - rt0;   // 100 MHz ticks
+        dbg_acc[7] = __builtin_readcyclecounter() - ct0;
+        dbg_acc[0] = rt0;                                        // absolute start of the main loop
+        dbg_acc[1] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);    // HW_ID
+        dbg_acc[2] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 20);   // XCC_ID
+        dbg_acc[3] = logical;
+        dbg_acc[4] = rt_kernel_entry;
+        for (int i = 0; i < DBG_SLOTS; ++i) attn_dbg[(blockIdx.x * 8 + wave) * DBG_SLOTS + i] = dbg_acc[i];
+    }
+#endif
+
+#ifdef ATTN_TIMING
+    if (blockIdx.x < DBG_WGS && lane == 0) attn_dbg[(blockIdx.x * 8 + wave) * DBG_SLOTS + 5] = __builtin_amdgcn_s_memrealtime();
+#endif
 }
 
 template <int DTYPE, int D, int NW, int MB, int BN, int STAGES, bool CAUSAL>
@@ -541,6 +552,13 @@ int attn_launch(const AttnLaunchArgs& a)
     if (a.dtype == 0) return a.d == 128 ? launch_d<0, 128>(a) : launch_d<0, 64>(a);
     return a.d == 128 ? launch_d<1, 128>(a) : launch_d<1, 64>(a);
 }
+
+#ifdef ATTN_TIMING
+extern "C" int attn_dbg_read(unsigned long long* host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(attn_dbg), sizeof(unsigned long long) * n);
+}
+#endif
 
 int attn_launch_tile_param(int d, int causal, int which)
 {
