@@ -54,6 +54,11 @@ constexpr float RESCALE_LOG2 = 8.0f;
 #define ATTN_FWIN 4
 #endif
 
+// Which wave group issues the global -> LDS copies (see COPY_WAVES in the kernel).
+#ifndef ATTN_COPY_GROUP
+#define ATTN_COPY_GROUP 0
+#endif
+
 // Element-type traits: MFMA flavour and fp32 -> 16-bit conversion (round to nearest even).
 template <int DTYPE> struct Elem;
 template <> struct Elem<0> {  // IEEE binary16
@@ -161,9 +166,11 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int STAGE_BYTES = 2 * TILE_BYTES;
     constexpr int RB = BN / 16;                 // 16-row blocks per tile
     constexpr int CHUNKS = TILE_BYTES / 1024;   // 1 KiB wave-transfers per tile
-    constexpr int CPW = CHUNKS / NW;            // ... per wave
-    constexpr int LPG = 2 * CPW;                // copies a wave issues per stage (K part + V part)
-    static_assert(CHUNKS % NW == 0, "tile must split evenly over the waves");
+    // Which waves issue the copies: 0 = all eight, 1 = group B only, 2 = group A only.
+    constexpr int COPY_WAVES = ATTN_COPY_GROUP == 0 ? NW : NW / 2;
+    constexpr int CPW = CHUNKS / COPY_WAVES;    // ... per copying wave
+    constexpr int LPG = 2 * CPW;                // copies such a wave issues per stage (K part + V part)
+    static_assert(CHUNKS % COPY_WAVES == 0, "tile must split evenly over the copying waves");
     static_assert(STAGES == 4, "the ring protocol below keeps four stages");
     static_assert(NW == 8, "two groups of four waves, one wave of each group per SIMD");
 
@@ -210,14 +217,17 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // sequence (their surplus rows are masked or never read).
     const unsigned k_lane_off = (lane & 15) * ROW_BYTES + (lane >> 4) * 16;
     const unsigned v_lane_off = (lane >> 2) * ROW_BYTES + (lane & 3) * 16;
+    const bool copies = ATTN_COPY_GROUP == 0 || (ATTN_COPY_GROUP == 1) == group_b;   // does this wave issue copies
+    const int cwave = ATTN_COPY_GROUP == 0 ? wave : (wave & (NW / 2 - 1));         // its index among the copying waves
     int piece_src[CPW], piece_dst[CPW];         // wave-uniform: source offset inside a tile, LDS offset inside a K or V slot
 #pragma unroll
     for (int i = 0; i < CPW; ++i) {
-        const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
+        const int wc = cwave * CPW + i, fg = wc / RB, rb = wc % RB;
         piece_src[i] = rb * 16 * ROW_BYTES + fg * 64;
         piece_dst[i] = wc * 1024;
     }
     auto issue_stage = [&](int s) __attribute__((always_inline)) {             // s = -1 is the stage that only brings K tile 0
+        if (!copies) return;
         const unsigned sbase = lds_base + ((s + STAGES) % STAGES) * STAGE_BYTES;
         if (s >= 0 && (s + 2) * BN <= N) {      // K tile s+1 and V tile s lie wholly inside the sequence
             const char* kt = kh + (size_t)(s + 1) * TILE_BYTES;
@@ -229,13 +239,13 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         } else {
 #pragma unroll
             for (int i = 0; i < CPW; ++i) {
-                const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
+                const int wc = cwave * CPW + i, fg = wc / RB, rb = wc % RB;
                 const int row = min(max((s + 1) * BN + rb * 16 + (lane & 15), 0), N - 1);
                 dma16(kh, (unsigned)(row * ROW_BYTES + fg * 64 + (lane >> 4) * 16), sbase + piece_dst[i]);
             }
 #pragma unroll
             for (int i = 0; i < CPW; ++i) {
-                const int wc = wave * CPW + i, fg = wc / RB, rb = wc % RB;
+                const int wc = cwave * CPW + i, fg = wc / RB, rb = wc % RB;
                 const int row = min(max(s * BN + rb * 16 + (lane >> 2), 0), N - 1);
                 dma16(vh, (unsigned)(row * ROW_BYTES + fg * 64 + (lane & 3) * 16), sbase + TILE_BYTES + piece_dst[i]);
             }
@@ -397,7 +407,9 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // to stage j, leaving only stage j+1's in flight) and nobody reads stage j-2 any more, so that
     // stage takes the copies of stage j+2.
     auto wait_stage = [&](int j) __attribute__((always_inline)) {
-        if (j + 1 < nt) wait_vmcnt<LPG>(); else wait_vmcnt<0>();
+        if (copies) {
+            if (j + 1 < nt) wait_vmcnt<LPG>(); else wait_vmcnt<0>();
+        }
         __builtin_amdgcn_s_barrier();
     };
     auto stage_ptr = [&](int s) __attribute__((always_inline)) -> const char* { return smem + ((s + STAGES) % STAGES) * STAGE_BYTES; };
@@ -453,8 +465,15 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             TSTAMP(t4);
             TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3); TACC(3, t3, t4);
         };
+        // (bottom-tested on purpose: with the exit test at the top the accumulators' loop-carried
+        // value is also live on the exit edge, the first MFMA of an iteration then cannot update it
+        // in place, and the compiler copies all 64 accumulator registers back every iteration)
         int j = 1;
-        for (; j < nt_w; ++j) iter_a(j);
+        if (j < nt_w) {
+            do {
+                iter_a(j);
+            } while (++j < nt_w);
+        }
         if (j < nt) wait_stage(j);                                                       // j == nt_w
         mfma_burst(std::true_type{}, std::false_type{}, stage_ptr(j - 1));               // U of the last tile
         if (j < nt && j + 2 < nt) issue_stage(j + 2);
@@ -479,7 +498,11 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             TACC(0, t0, t1); TACC(2, t1, t2); TACC(3, t2, t3); TACC(1, t3, t4);
         };
         int j = 0;
-        for (; j + 1 < nt_w; ++j) iter_b(j);
+        if (j + 1 < nt_w) {
+            do {
+                iter_b(j);
+            } while (++j + 1 < nt_w);
+        }
         wait_stage(j);                                                                   // j == nt_w - 1
         if (j + 2 < nt) issue_stage(j + 2);
         softmax_tile(j);
