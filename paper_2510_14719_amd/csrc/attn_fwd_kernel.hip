@@ -54,6 +54,11 @@ constexpr float RESCALE_LOG2 = 8.0f;
 #define ATTN_FWIN 4
 #endif
 
+// Independent accumulation chains of the row sum (see softmax_tile).
+#ifndef ATTN_SUMCHAINS
+#define ATTN_SUMCHAINS 4
+#endif
+
 // Which wave group issues the global -> LDS copies (see COPY_WAVES in the kernel).
 #ifndef ATTN_COPY_GROUP
 #define ATTN_COPY_GROUP 0
@@ -107,11 +112,16 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 
 #ifdef ATTN_TIMING
 // Profiling builds only: per-wave cycle totals of the main-loop sections of the first workgroups.
-constexpr int DBG_WGS = 1024, DBG_SLOTS = 8;
+constexpr int DBG_WGS = 1024, DBG_SLOTS = ATTN_TIMING >= 3 ? 32 : 8;
 __device__ unsigned long long attn_dbg[DBG_WGS * 8 * DBG_SLOTS];
 #if ATTN_TIMING >= 2
-#define TSTAMP(var) const unsigned long long var = __builtin_readcyclecounter()
+#define TSTAMP(var) unsigned long long var; __builtin_amdgcn_sched_barrier(0); \
+    asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(var) :: "memory"); __builtin_amdgcn_sched_barrier(0)
+#if ATTN_TIMING >= 3   // absolute stamps of iterations 100..103
+#define TACC(slot, a, b) if (j >= 100 && j < 104) { dbg_acc[8 + (j - 100) * 5 + slot] = (a); if (slot == 3) dbg_acc[8 + (j - 100) * 5 + 4] = (b); }
+#else
 #define TACC(slot, a, b) dbg_acc[slot] += (b) - (a)
+#endif
 #else
 #define TSTAMP(var)
 #define TACC(slot, a, b)
@@ -317,11 +327,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             if (f < NU) fr[f] = read_vf(sv, f / (2 * DB), (f / DB) % 2, f % DB);
             else fr[f] = read_kf(sk, (f - NU) % KB, (f - NU) / KB);
         };
-#pragma unroll
-        for (int f = 0; f < FWIN; ++f) fetch(f);
-#pragma unroll
-        for (int f = 0; f < NF; ++f) {
-            if (f + FWIN < NF) fetch(f + FWIN);
+        auto run_mfma = [&](int f) __attribute__((always_inline)) {
             if (f < NU) {
                 const int kb = f / (2 * DB), ks = (f / DB) % 2, db = f % DB;
 #pragma unroll
@@ -338,6 +344,13 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                     S[mb][kb] = E::mfma(fr[f], Qf[mb][kk], kk == 0 ? f32x16(0.f) : S[mb][kb]);
                 }
             }
+        };
+#pragma unroll
+        for (int f = 0; f < FWIN; ++f) fetch(f);
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            if (f + FWIN < NF) fetch(f + FWIN);
+            run_mfma(f);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -380,7 +393,11 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             alpha[mb] = __builtin_amdgcn_exp2f((m_old - m_use) * scale_log2e);
             const float neg_mc = -m_use * scale_log2e;
             m_run[mb] = m_use;
-            float sum0 = 0.f, sum1 = 0.f;       // two chains: the pair sums do not wait for each other
+            // independent chains: a dot2 accumulate has a dependent latency of about four issue slots
+            constexpr int NCH = ATTN_SUMCHAINS;
+            float sum[NCH];
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) sum[c] = 0.f;
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -389,9 +406,12 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                     const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][kb][2 * t + 1], scale_log2e, neg_mc));
                     const unsigned w = E::pack2(p0, p1);
                     pw[mb][kb * 8 + t] = w;
-                    if (t & 1) sum1 = E::add_pair(w, sum1); else sum0 = E::add_pair(w, sum0);
+                    sum[t % NCH] = E::add_pair(w, sum[t % NCH]);
                 }
-            l_run[mb] = l_run[mb] * alpha[mb] + (sum0 + sum1);
+            float tile_sum = sum[0];
+#pragma unroll
+            for (int c = 1; c < NCH; ++c) tile_sum += sum[c];
+            l_run[mb] = l_run[mb] * alpha[mb] + tile_sum;
         }
         if (__builtin_amdgcn_ballot_w64(upd_any) != 0) {
             // whole-vector multiplies: element-wise updates would make the compiler split the
@@ -442,7 +462,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 
     __builtin_amdgcn_s_barrier();               // stages -1, 0, 1 are complete for every wave
 #ifdef ATTN_TIMING
-    unsigned long long dbg_acc[DBG_SLOTS] = {0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long dbg_acc[DBG_SLOTS] = {};
     const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime(), ct0 = __builtin_readcyclecounter();
 #endif
     // Each group's steady state is one loop with a single code path (the first and last tile and the
@@ -518,11 +538,13 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         dbg_acc[5] = nt;
         dbg_acc[6] = __builtin_amdgcn_s_memrealtime() - rt0;   // 100 MHz ticks
         dbg_acc[7] = __builtin_readcyclecounter() - ct0;
+#if ATTN_TIMING == 1
         dbg_acc[0] = rt0;                                        // absolute start of the main loop
         dbg_acc[1] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);    // HW_ID
         dbg_acc[2] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 20);   // XCC_ID
         dbg_acc[3] = logical;
         dbg_acc[4] = rt_kernel_entry;
+#endif
         for (int i = 0; i < DBG_SLOTS; ++i) attn_dbg[(blockIdx.x * 8 + wave) * DBG_SLOTS + i] = dbg_acc[i];
     }
 #endif
