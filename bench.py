@@ -55,6 +55,26 @@ def cpu_baseline(w, budget_heads: int = 2) -> dict:
             "sample": "%d of %d heads of %s (all N=%d query rows of each), fp64" % (heads, w.B * w.H, w.name, w.N)}
 
 
+def mfma_sustained(binding, torch, dtype: int, stream, launches: int = 150, warm: int = 60) -> dict:
+    """Register-only MFMA stream of the library's probe: what the matrix cores sustain on this GPU
+    with zero operands (nothing toggles) and with pseudo-random operands (toggling of real data)."""
+    wgs = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(binding.load_library().attn_fwd_mfma_probe_sink_floats(wgs), dtype=torch.float32, device="cuda")
+    iters = 4000    # about as long as one attention launch of the headline workload
+    out = {"workgroups": wgs, "mfmas_per_wave": iters * 8, "launches": launches}
+    for name, rnd in (("zero_operands", False), ("random_operands", True)):
+        for _ in range(warm):
+            binding.mfma_probe(sink, wgs, iters, rnd, dtype, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(launches):
+            flops = binding.mfma_probe(sink, wgs, iters, rnd, dtype, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        out[name] = flops * launches / (e0.elapsed_time(e1) * 1e-3) * 1e-12
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +82,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=25)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the register-only MFMA stream that measures the sustained matrix-core rate")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (reference point for "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -156,6 +178,13 @@ def main() -> int:
         "context": {"paper_h100_fp16_mha_tflops": 654.0,
                     "paper_workload": "H100 SXM5, L=16384, batch 4, d=128 (Section 5.6); other hardware, not a target"},
     }
+    if not args.no_mfma_probe:
+        # outside the timed region: the measured MFMA-only rates next to the datasheet peak
+        sus = mfma_sustained(binding, torch, w.dtype, stream)
+        sus["unit"] = "TFLOP/s"
+        sus["frac_of_random_operands"] = achieved / sus["random_operands"]
+        sus["frac_of_zero_operands"] = achieved / sus["zero_operands"]
+        out["roofline"]["mfma_only_measured"] = sus
     if parity is not None:
         out["parity_sample"] = parity
     if not args.no_cpu_baseline:

@@ -87,6 +87,26 @@ int attn_fwd_version(void);
  */
 int attn_fwd_tile_param(int d, int causal, int which);
 
+/*
+ * Measurement aid for the MFMA roofline (not part of the attention path).  Enqueues on `stream` one
+ * kernel of `workgroups` workgroups (two waves per SIMD of a CU, like the attention kernel) in which
+ * every wave issues iters*8 back-to-back 32x32x16 MFMAs of the given element type on operands held in
+ * registers: no memory traffic, no vector work.  random_operands = 0 uses all-zero operands (nothing
+ * toggles; the clock stays at its maximum), non-zero uses pseudo-random finite values (the toggling
+ * of real inputs; the clock settles where the power management puts it).  The caller times the launch
+ * (events on `stream`) and divides attn_fwd_mfma_probe_flops(workgroups, iters) by the duration.
+ *   sink   DEVICE pointer, written: attn_fwd_mfma_probe_sink_floats(workgroups) floats, 4-byte aligned.
+ * Returns ATTN_FWD_OK, ATTN_FWD_ERR_NULL, ATTN_FWD_ERR_SHAPE (workgroups outside 1..65536, iters outside
+ * 1..2^24, unknown dtype), ATTN_FWD_ERR_ALIGN or ATTN_FWD_ERR_LAUNCH; validation precedes any HIP call.
+ */
+int attn_fwd_mfma_probe(float *sink, int workgroups, int iters, int random_operands, int dtype, void *stream);
+
+/* Floating-point operations one such launch executes (0.0 for non-positive arguments). */
+double attn_fwd_mfma_probe_flops(int workgroups, int iters);
+
+/* Number of floats the launch writes to `sink` (-1 for workgroups outside 1..65536). */
+int attn_fwd_mfma_probe_sink_floats(int workgroups);
+
 #ifdef __cplusplus
 }
 #endif

@@ -55,6 +55,12 @@ def load_library() -> ctypes.CDLL:
         lib.attn_fwd_version.argtypes = []
         lib.attn_fwd_tile_param.restype = ci
         lib.attn_fwd_tile_param.argtypes = [ci, ci, ci]
+        lib.attn_fwd_mfma_probe.restype = ci
+        lib.attn_fwd_mfma_probe.argtypes = [vp, ci, ci, ci, ci, vp]
+        lib.attn_fwd_mfma_probe_flops.restype = ctypes.c_double
+        lib.attn_fwd_mfma_probe_flops.argtypes = [ci, ci]
+        lib.attn_fwd_mfma_probe_sink_floats.restype = ci
+        lib.attn_fwd_mfma_probe_sink_floats.argtypes = [ci]
         _lib = lib
     return _lib
 
@@ -127,3 +133,16 @@ def tile_params(d: int, causal: bool = False) -> dict:
     lib = load_library()
     return {"BM": lib.attn_fwd_tile_param(d, int(causal), 0), "BN": lib.attn_fwd_tile_param(d, int(causal), 1),
             "stages": lib.attn_fwd_tile_param(d, int(causal), 2), "threads": lib.attn_fwd_tile_param(d, int(causal), 3)}
+
+
+def mfma_probe(sink, workgroups: int, iters: int, random_operands: bool, dtype: int = FP16, stream=None) -> float:
+    """``attn_fwd_mfma_probe`` of the C ABI: enqueue the register-only MFMA stream; returns its flop count."""
+    lib = load_library()
+    need = lib.attn_fwd_mfma_probe_sink_floats(int(workgroups))
+    if not isinstance(sink, int) and sink.numel() * sink.element_size() < 4 * need:
+        raise ValueError("sink needs %d floats" % need)
+    rc = int(lib.attn_fwd_mfma_probe(_ptr(sink), int(workgroups), int(iters), int(bool(random_operands)), int(dtype),
+                                     _stream_handle(stream)))
+    if rc != 0:
+        raise AttnFwdError(rc, strerror(rc))
+    return float(lib.attn_fwd_mfma_probe_flops(int(workgroups), int(iters)))

@@ -82,4 +82,25 @@ int attn_fwd_version(void) { return 100; }
 
 int attn_fwd_tile_param(int d, int causal, int which) { return attn_launch_tile_param(d, causal, which); }
 
+int attn_fwd_mfma_probe(float* sink, int workgroups, int iters, int random_operands, int dtype, void* stream)
+{
+    if (!sink) return ATTN_FWD_ERR_NULL;
+    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24)) return ATTN_FWD_ERR_SHAPE;
+    if (dtype != ATTN_FWD_FP16 && dtype != ATTN_FWD_BF16) return ATTN_FWD_ERR_SHAPE;
+    if (reinterpret_cast<std::uintptr_t>(sink) & 3u) return ATTN_FWD_ERR_ALIGN;
+    return mfma_probe_launch(sink, workgroups, iters, random_operands != 0, dtype, stream) == 0 ? ATTN_FWD_OK : ATTN_FWD_ERR_LAUNCH;
+}
+
+double attn_fwd_mfma_probe_flops(int workgroups, int iters)
+{
+    if (workgroups < 1 || iters < 1) return 0.0;
+    return mfma_probe_flops(workgroups, iters);
+}
+
+int attn_fwd_mfma_probe_sink_floats(int workgroups)
+{
+    if (workgroups < 1 || workgroups > 65536) return -1;
+    return workgroups * mfma_probe_threads();
+}
+
 }  // extern "C"

@@ -33,3 +33,9 @@ int attn_launch(const AttnLaunchArgs& a);
 
 // Query rows per workgroup (0), keys per tile (1), LDS stages (2), threads per workgroup (3).
 int attn_launch_tile_param(int d, int causal, int which);
+
+// Register-only MFMA stream (mfma_probe.hip): `workgroups` workgroups of mfma_probe_threads() threads,
+// every wave issuing iters * 8 MFMAs of the given element type; one float per thread is written to sink.
+int mfma_probe_launch(float* sink, int workgroups, int iters, int random_operands, int dtype, void* stream);
+double mfma_probe_flops(int workgroups, int iters);
+int mfma_probe_threads(void);

@@ -72,3 +72,18 @@ def test_entry_points_return_argument_errors_without_launching(lib):
     assert lib.attn_fwd_f16(None, None, None, None, None, 1, 1, 64, 64, 0.125, 0, None) == -1
     assert lib.attn_fwd_bf16(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 1, 1, 64, 48, 0.125, 0, None) == -2
     assert lib.attn_fwd(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 1, 1, 64, 64, 0.125, 0, None, 7) == -2
+
+
+def test_mfma_probe_validation_needs_no_gpu(lib):
+    f = lib.attn_fwd_mfma_probe
+    assert f(None, 256, 100, 1, 0, None) == -1
+    assert f(0x10000000, 0, 100, 1, 0, None) == -2
+    assert f(0x10000000, 70000, 100, 1, 0, None) == -2
+    assert f(0x10000000, 256, 0, 1, 0, None) == -2
+    assert f(0x10000000, 256, 100, 1, 5, None) == -2
+    assert f(0x10000002, 256, 100, 1, 0, None) == -4
+    assert lib.attn_fwd_mfma_probe_sink_floats(256) == 256 * 512
+    assert lib.attn_fwd_mfma_probe_sink_floats(0) == -1
+    # 8 waves x iters x 8 MFMAs x 2*32*32*16 flops per workgroup
+    assert lib.attn_fwd_mfma_probe_flops(2, 10) == 2 * 8 * 10 * 8 * 32768.0
+    assert lib.attn_fwd_mfma_probe_flops(0, 10) == 0.0
