@@ -28,6 +28,10 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {0: 2500.0, 1: 2500.0}   # MI355X dense MFMA peak, fp16 and bf16
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each scaled by
+# what the counter reads for a 1 GiB copy); a profile's figure, not measured by this script.
+MEASURED_TRAFFIC = {"c4": ((163994.6 * 2.000 + 67133.9 * 1.000) * 1024.0, "profiles/attn_fwd_c4_fp16_noncausal.md")}
+
 
 def describe(w) -> str:
     return "%s: B=%d H=%d N=%d d=%d %s %s%s" % (
@@ -173,7 +177,9 @@ def main() -> int:
                    "flops_per_step": w.flops, "wall_s_timed_region": wall},
         "frac_of_mfma_peak": tflops / peak,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": None,
+                     "traffic": MEASURED_TRAFFIC[w.name][0] if w.name in MEASURED_TRAFFIC else None,
+                     "traffic_unit": "bytes of HBM traffic per launch (rocprofv3 counters, see %s)"
+                                     % MEASURED_TRAFFIC[w.name][1] if w.name in MEASURED_TRAFFIC else None,
                      "kernel_ms": {"mean": kern_ms, "median": statistics.median(per_launch), "min": min(per_launch)}},
         "context": {"paper_h100_fp16_mha_tflops": 654.0,
                     "paper_workload": "H100 SXM5, L=16384, batch 4, d=128 (Section 5.6); other hardware, not a target"},
