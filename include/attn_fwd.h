@@ -88,6 +88,17 @@ int attn_fwd_version(void);
 int attn_fwd_tile_param(int d, int causal, int which);
 
 /*
+ * The static tile schedule of the launch (host-side copy of what the kernel evaluates; the paper's
+ * Section 4.2 describes persistent kernels that walk a tile queue).  A launch covers `total` logical
+ * tiles (logical tile t = (batch*head t / nqt, query tile t % nqt), nqt = ceil(N / BM); under the
+ * causal mask the query tiles of a head are numbered from the longest to the shortest) with `grid`
+ * workgroups, 1 <= grid <= total.  Returns the logical tile workgroup `block` processes in round
+ * `round` (0, 1, ...), -1 when it has none in that round or any later one, -2 for arguments out of
+ * range.  Every logical tile belongs to exactly one (block, round).
+ */
+int attn_fwd_tile_schedule(int total, int grid, int block, int round);
+
+/*
  * Measurement aid for the MFMA roofline (not part of the attention path).  Enqueues on `stream` one
  * kernel of `workgroups` workgroups (two waves per SIMD of a CU, like the attention kernel) in which
  * every wave issues iters*8 back-to-back 32x32x16 MFMAs of the given element type on operands held in

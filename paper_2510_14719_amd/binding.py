@@ -55,6 +55,8 @@ def load_library() -> ctypes.CDLL:
         lib.attn_fwd_version.argtypes = []
         lib.attn_fwd_tile_param.restype = ci
         lib.attn_fwd_tile_param.argtypes = [ci, ci, ci]
+        lib.attn_fwd_tile_schedule.restype = ci
+        lib.attn_fwd_tile_schedule.argtypes = [ci, ci, ci, ci]
         lib.attn_fwd_mfma_probe.restype = ci
         lib.attn_fwd_mfma_probe.argtypes = [vp, ci, ci, ci, ci, vp]
         lib.attn_fwd_mfma_probe_flops.restype = ctypes.c_double

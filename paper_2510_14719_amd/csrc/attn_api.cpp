@@ -7,6 +7,7 @@
 #include <cstdint>
 
 #include "attn_launch.h"
+#include "tile_schedule.h"
 
 namespace {
 
@@ -81,6 +82,12 @@ const char* attn_fwd_strerror(int code)
 int attn_fwd_version(void) { return 100; }
 
 int attn_fwd_tile_param(int d, int causal, int which) { return attn_launch_tile_param(d, causal, which); }
+
+int attn_fwd_tile_schedule(int total, int grid, int block, int round)
+{
+    if (total < 1 || grid < 1 || grid > total || block < 0 || block >= grid || round < 0) return -2;
+    return tile_schedule(total, grid, block, round);
+}
 
 int attn_fwd_mfma_probe(float* sink, int workgroups, int iters, int random_operands, int dtype, void* stream)
 {

@@ -34,6 +34,7 @@
 #include <type_traits>
 
 #include "attn_launch.h"
+#include "tile_schedule.h"
 
 namespace {
 
@@ -57,6 +58,11 @@ constexpr float RESCALE_LOG2 = 8.0f;
 // Independent accumulation chains of the row sum (see softmax_tile).
 #ifndef ATTN_SUMCHAINS
 #define ATTN_SUMCHAINS 4
+#endif
+
+// 1: launch one workgroup per resident slot and let each walk several tiles; 0: one workgroup per tile.
+#ifndef ATTN_PERSISTENT
+#define ATTN_PERSISTENT 1
 #endif
 
 // Which wave group issues the global -> LDS copies (see COPY_WAVES in the kernel).
@@ -98,12 +104,21 @@ template <> struct Elem<1> {  // bfloat16
     }
 };
 
+// A wave-uniform pointer, moved into scalar registers.
+template <typename T> __device__ __forceinline__ T* uniform_ptr(T* p) {
+    const unsigned long long a = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+    return reinterpret_cast<T*>(((unsigned long long)hi << 32) | lo);
+}
+
 // 16 bytes per lane from global memory straight into the LDS: lane L's bytes land at
 // lds_addr + 16*L.  The compiler is not told about the transfer (it would otherwise wait for ALL
 // outstanding loads before every LDS read); completion is tracked by hand with s_waitcnt vmcnt.
 __device__ __forceinline__ void dma16(const void* gbase, unsigned voff, unsigned lds_addr) {
+    // (base and LDS address are wave-uniform; the readfirstlanes are free when the compiler already
+    // holds them in scalar registers and put them there when it chose vector registers)
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(uniform_ptr(gbase)) : "memory");
 }
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
@@ -151,15 +166,6 @@ __device__ __forceinline__ float xor32_sum(float x) {
     return a + b;
 }
 
-// Workgroups are handed to the 8 XCDs round-robin; give every XCD a contiguous range of logical
-// tiles so that the workgroups resident on one XCD stream the same head's K/V through its L2.
-__device__ __forceinline__ int xcd_remap(int id, int total) {
-    constexpr int XCDS = 8;
-    const int q = total / XCDS, r = total % XCDS;
-    const int x = id % XCDS, slot = id / XCDS;
-    return x * q + (x < r ? x : r) + slot;
-}
-
 template <int DTYPE, int D, int NW, int MB, int BN, int STAGES, bool CAUSAL>
 __global__ __launch_bounds__(NW * 64)
 void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -168,6 +174,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 {
     typedef Elem<DTYPE> E;
     constexpr int BM = NW * MB * 32;            // query rows per workgroup
+    constexpr bool PERSIST = ATTN_PERSISTENT && D == 128 && CAUSAL;
     constexpr int KB = BN / 32;                 // 32-key blocks per K/V tile
     constexpr int KK = D / 16;                  // contraction steps of Q K^T
     constexpr int DB = D / 32;                  // 32-wide feature blocks of O
@@ -195,27 +202,39 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     const int lr = lane & 31, g = lane >> 5;
     const bool group_b = wave >= NW / 2;        // waves w and w + 4 share a SIMD
 
-    // ---- which (batch*head, query tile) this workgroup owns
-    const int logical = xcd_remap(blockIdx.x, total);
-    const int bh = logical / nqt;
-    int qt = logical - bh * nqt;
-    if (CAUSAL) qt = nqt - 1 - qt;              // long rows first
-    const int q0 = qt * BM;
-    const int wq0 = q0 + wave * (MB * 32);      // first query row of this wave
-
-    const size_t head_off = (size_t)bh * N * D;
-    const uint16_t* qh = q + head_off;
-    const char* kh = reinterpret_cast<const char*>(k + head_off);
-    const char* vh = reinterpret_cast<const char*>(v + head_off);
-
-    // ---- number of K/V tiles the workgroup walks, and the number this wave computes on
-    int nt = (N + BN - 1) / BN;
-    if (CAUSAL) {
-        const int last_q = min(q0 + BM, N) - 1;
-        nt = min(nt, last_q / BN + 1);
-    }
-    int nt_w = nt;
-    if (CAUSAL) nt_w = min(nt, (wq0 + MB * 32 - 1) / BN + 1);   // later tiles are wholly hidden from this wave's rows
+    // ---- which (batch*head, query tile) the workgroup works on: set per round of the tile schedule
+    int round = 0;
+    int logical __attribute__((unused)), bh, wq0, nt, nt_w;             // nt: K/V tiles the workgroup walks; nt_w: those this wave computes on
+    size_t head_off;
+    const uint16_t* qh;
+    const char *kh, *vh;
+    auto set_tile = [&](int tile) __attribute__((always_inline)) {
+        tile = __builtin_amdgcn_readfirstlane(tile);   // wave-uniform by construction; keeps all of the below in SGPRs
+        logical = tile;
+        bh = __builtin_amdgcn_readfirstlane(tile / nqt);   // (the division runs on the vector ALU)
+        int qt = tile - bh * nqt;
+        if (CAUSAL) qt = nqt - 1 - qt;          // long rows first
+        const int q0 = qt * BM;
+        wq0 = q0 + wave * (MB * 32);            // first query row of this wave
+        head_off = (size_t)bh * N * D;
+        qh = q + head_off;
+        kh = reinterpret_cast<const char*>(k + head_off);
+        vh = reinterpret_cast<const char*>(v + head_off);
+        nt = (N + BN - 1) / BN;
+        if (CAUSAL) {
+            const int last_q = min(q0 + BM, N) - 1;
+            nt = min(nt, last_q / BN + 1);
+        }
+        nt_w = nt;
+        if (CAUSAL) nt_w = min(nt, (wq0 + MB * 32 - 1) / BN + 1);   // later tiles are wholly hidden from this wave's rows
+        // All of these are wave-uniform; say so, or values that cross the tile loop end up in vector registers.
+        nt = __builtin_amdgcn_readfirstlane(nt);
+        nt_w = __builtin_amdgcn_readfirstlane(nt_w);
+        wq0 = __builtin_amdgcn_readfirstlane(wq0);
+        kh = uniform_ptr(kh);
+        vh = uniform_ptr(vh);
+    };
+    set_tile(tile_schedule(total, (int)gridDim.x, (int)blockIdx.x, 0));   // the launcher keeps grid <= total
 
     // ---- global -> LDS copies.  Stage s of the ring holds K tile s+1 and V tile s: the pair that one
     // MFMA burst reads (U_s needs V_s, T_{s+1} needs K_{s+1}).  A wave moves CPW 1 KiB pieces of each.
@@ -262,38 +281,26 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         }
     };
 
-    // ---- prologue: three stages in flight, Q fragments into registers
-    issue_stage(-1);
-    issue_stage(0);
-    issue_stage(1);
-
+    // ---- prologue of a tile: three stages in flight, Q fragments into registers
     s16x8 Qf[MB][KK];
+    auto prologue = [&]() __attribute__((always_inline)) {
+        issue_stage(-1);
+        issue_stage(0);
+        issue_stage(1);
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        const int row = min(wq0 + mb * 32 + lr, N - 1);
-        const uint16_t* qr = qh + (size_t)row * D;
+        for (int mb = 0; mb < MB; ++mb) {
+            const int row = min(wq0 + mb * 32 + lr, N - 1);
+            const uint16_t* qr = qh + (size_t)row * D;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
-            Qf[mb][kk] = *reinterpret_cast<const s16x8*>(qr + (kk * 2 + g) * 8);
-    }
-    // Use the Q fragments once here: the compiler then waits for their loads before the loop instead
-    // of inside it, where its vmcnt(0) would also wait for the K/V copies issued a moment earlier.
-    // (The Q loads were issued after the copies above, so this wait also covers stages -1, 0 and 1.)
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) asm volatile("" :: "v"(Qf[mb][kk]));
+            for (int kk = 0; kk < KK; ++kk)
+                Qf[mb][kk] = *reinterpret_cast<const s16x8*>(qr + (kk * 2 + g) * 8);
+        }
+    };
+    prologue();
 
     f32x16 O[MB][DB], S[MB][KB];
     unsigned pw[MB][KB * 8];                    // P of the current tile as packed 16-bit pairs
     float m_run[MB], l_run[MB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        m_run[mb] = -__builtin_inff();
-        l_run[mb] = 0.f;
-#pragma unroll
-        for (int db = 0; db < DB; ++db) O[mb][db] = f32x16(0.f);
-    }
 
     // per-lane LDS read offsets (the rest of every address is an immediate)
     const int k_lane = (lr >> 4) * 1024 + g * 256 + (lr & 15) * 16;
@@ -436,14 +443,14 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 
     // ---- epilogue: normalise, write O (16-bit) and LSE (natural log).  Expanded at the end of each
     // group's code path, so that the accumulators of the two paths never have to meet in one register set.
-    auto epilogue = [&]() __attribute__((always_inline)) {
-    uint16_t* oh = o + head_off;
-    float* lh = lse + (size_t)bh * N;
+    auto epilogue = [&](size_t ep_head_off, int ep_bh, int ep_wq0) __attribute__((always_inline)) {
+    uint16_t* oh = o + ep_head_off;
+    float* lh = lse + (size_t)ep_bh * N;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const float l_tot = xor32_sum(l_run[mb]);
         const float inv = 1.0f / l_tot;
-        const int row = wq0 + mb * 32 + lr;
+        const int row = ep_wq0 + mb * 32 + lr;
         if (row < N) {
             if (g == 0) lh[row] = m_run[mb] * scale + __builtin_logf(l_tot);
             uint16_t* orow = oh + (size_t)row * D;
@@ -460,10 +467,52 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     }
     };
 
-    __builtin_amdgcn_s_barrier();               // stages -1, 0, 1 are complete for every wave
+    // ---- end of a tile: when the schedule has another tile for this workgroup, its prologue is issued
+    // first (after a barrier: every wave is then done reading the ring), so that its copies and Q
+    // loads are in flight while the epilogue of the finished tile normalises and stores.
+    bool more = true;
+    auto finish_tile = [&]() __attribute__((always_inline)) {
+        const size_t ep_head_off = head_off;
+        const int ep_bh = bh, ep_wq0 = wq0;
+        // (at d = 64 two workgroups share a CU and cover each other's prologue and epilogue, and the
+        // next tile's Q fragments would cost the registers that let the two co-reside; without the
+        // causal mask the tiles are equally long and there is nothing to balance: one tile per workgroup)
+        const int next = PERSIST ? tile_schedule(total, (int)gridDim.x, (int)blockIdx.x, ++round) : -1;
+        more = next >= 0;
+        if (more) {
+            __builtin_amdgcn_s_barrier();
+            set_tile(next);
+            prologue();
+        }
+        epilogue(ep_head_off, ep_bh, ep_wq0);
+    };
+
 #ifdef ATTN_TIMING
     unsigned long long dbg_acc[DBG_SLOTS] = {};
-    const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime(), ct0 = __builtin_readcyclecounter();
+    unsigned long long rt0 = 0, ct0 = 0;
+#endif
+    do {
+    // (the tile's coordinates are derived afresh from the round number: only that number and the Q
+    // fragments cross from one tile to the next, everything else restarts from scalar registers)
+    set_tile(tile_schedule(total, (int)gridDim.x, (int)blockIdx.x, __builtin_amdgcn_readfirstlane(round)));
+    // Use the Q fragments once here: the compiler then waits for their loads before the loop instead
+    // of inside it, where its vmcnt(0) would also wait for the K/V copies issued a moment earlier.
+    // (The Q loads were issued after the copies of the prologue, so this wait also covers stages -1, 0, 1.)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) asm volatile("" :: "v"(Qf[mb][kk]));
+    wait_vmcnt<0>();
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        m_run[mb] = -__builtin_inff();
+        l_run[mb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) O[mb][db] = f32x16(0.f);
+    }
+    __builtin_amdgcn_s_barrier();               // stages -1, 0, 1 are complete for every wave
+#ifdef ATTN_TIMING
+    rt0 = __builtin_amdgcn_s_memrealtime(); ct0 = __builtin_readcyclecounter();
 #endif
     // Each group's steady state is one loop with a single code path (the first and last tile and the
     // idle tail of a causal wave are peeled off), so the accumulators stay in place across iterations.
@@ -501,7 +550,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             wait_stage(j);
             if (j + 2 < nt) issue_stage(j + 2);
         }
-        epilogue();
+        finish_tile();
     } else {
         // group B, iteration j: C_j then [U_j, T_{j+1}]; both contractions read stage j
         mfma_burst(std::false_type{}, std::true_type{}, stage_ptr(-1));                  // T_0
@@ -531,8 +580,9 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             wait_stage(j);
             if (j + 2 < nt) issue_stage(j + 2);
         }
-        epilogue();
+        finish_tile();
     }
+    } while (more);
 #ifdef ATTN_TIMING
     if (blockIdx.x < DBG_WGS && lane == 0) {
         dbg_acc[5] = nt;
@@ -568,6 +618,20 @@ int launch(const AttnLaunchArgs& a)
     }
     const int nqt = (a.N + BM - 1) / BM;
     const long long total = (long long)nqt * a.B * a.H;
+    // Persistent launch for the causal kernel at d = 128: as many workgroups as the chip holds at once
+    // (one per CU: the LDS ring takes 128 KiB), each walking its share of the tile schedule.  Measured:
+    // +2.5 % on causal N = 8192 (balanced tile lengths, next prologue under the epilogue); without the
+    // mask all tiles are equally long, the hardware's own dispatch is as good and the plain launch
+    // compiles to a slightly tighter main loop, so it keeps one tile per workgroup.
+    long long grid = total;
+    if (ATTN_PERSISTENT && D == 128 && CAUSAL) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+            return -1;
+        const long long resident = (long long)cus * ((160 * 1024) / smem);
+        if (grid > resident) grid = resident;
+    }
     const float log2e = 1.4426950408889634f;
     const uint16_t* q = (const uint16_t*)a.q;
     const uint16_t* k = (const uint16_t*)a.k;
@@ -578,7 +642,7 @@ int launch(const AttnLaunchArgs& a)
     float scale = a.scale, scale_log2e = a.scale * log2e;
     void* args[] = {&q, &k, &v, &o, &lse, &N, &nqt_arg, &total_arg, &scale, &scale_log2e};
     // the launch's own status, not hipGetLastError(): that one also reports stale errors of unrelated calls
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3((unsigned)total), dim3(NW * 64),
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3((unsigned)grid), dim3(NW * 64),
                                          args, smem, (hipStream_t)a.stream);
     return e == hipSuccess ? 0 : -1;
 }

@@ -40,6 +40,13 @@ def test_small_shapes_full_compare(G, oracle, N, d, causal, dtype):
     _full(G, oracle, 2, 3, N, d, dtype, causal, seed=50 + N)
 
 
+@pytest.mark.parametrize("causal,dtype", [(False, I.FP16), (True, I.BF16)])
+def test_more_tiles_than_resident_workgroups(G, oracle, causal, dtype):
+    # 650 query tiles at d = 128: a persistent launch walks up to three rounds of its tile schedule,
+    # the last one partial, each workgroup switching head and query tile between rounds
+    _full(G, oracle, 5, 26, 1100, 128, dtype, causal, seed=77, what="multi-round")
+
+
 def test_config_c1(G, oracle):
     w = I.WORKLOADS["c1"]
     _full(G, oracle, w.B, w.H, w.N, w.d, w.dtype, w.causal, w.seed, what="c1")
