@@ -64,6 +64,10 @@ constexpr float RESCALE_LOG2 = 8.0f;
 #ifndef ATTN_PERSISTENT
 #define ATTN_PERSISTENT 1
 #endif
+// Longest sequence for which the non-causal d = 128 launch is persistent too (see launch_d).
+#ifndef ATTN_PERSIST_NC_MAX_N
+#define ATTN_PERSIST_NC_MAX_N 1024
+#endif
 
 // Which wave group issues the global -> LDS copies (see COPY_WAVES in the kernel).
 #ifndef ATTN_COPY_GROUP
@@ -166,7 +170,7 @@ __device__ __forceinline__ float xor32_sum(float x) {
     return a + b;
 }
 
-template <int DTYPE, int D, int NW, int MB, int BN, int STAGES, bool CAUSAL>
+template <int DTYPE, int D, int NW, int MB, int BN, int STAGES, bool CAUSAL, bool PERSIST>
 __global__ __launch_bounds__(NW * 64)
 void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                      uint16_t* __restrict__ o, float* __restrict__ lse, int N, int nqt, int total,
@@ -174,7 +178,6 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 {
     typedef Elem<DTYPE> E;
     constexpr int BM = NW * MB * 32;            // query rows per workgroup
-    constexpr bool PERSIST = ATTN_PERSISTENT && D == 128 && CAUSAL;
     constexpr int KB = BN / 32;                 // 32-key blocks per K/V tile
     constexpr int KK = D / 16;                  // contraction steps of Q K^T
     constexpr int DB = D / 32;                  // 32-wide feature blocks of O
@@ -474,9 +477,6 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     auto finish_tile = [&]() __attribute__((always_inline)) {
         const size_t ep_head_off = head_off;
         const int ep_bh = bh, ep_wq0 = wq0;
-        // (at d = 64 two workgroups share a CU and cover each other's prologue and epilogue, and the
-        // next tile's Q fragments would cost the registers that let the two co-reside; without the
-        // causal mask the tiles are equally long and there is nothing to balance: one tile per workgroup)
         const int next = PERSIST ? tile_schedule(total, (int)gridDim.x, (int)blockIdx.x, ++round) : -1;
         more = next >= 0;
         if (more) {
@@ -604,12 +604,12 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 #endif
 }
 
-template <int DTYPE, int D, int NW, int MB, int BN, int STAGES, bool CAUSAL>
+template <int DTYPE, int D, int NW, int MB, int BN, int STAGES, bool CAUSAL, bool PERSIST>
 int launch(const AttnLaunchArgs& a)
 {
     constexpr int BM = NW * MB * 32;
     constexpr int smem = STAGES * 2 * BN * D * 2;
-    auto kern = attn_fwd_kernel<DTYPE, D, NW, MB, BN, STAGES, CAUSAL>;
+    auto kern = attn_fwd_kernel<DTYPE, D, NW, MB, BN, STAGES, CAUSAL, PERSIST>;
     static bool attr_set = false;   // idempotent; a race only repeats the call
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
@@ -618,13 +618,10 @@ int launch(const AttnLaunchArgs& a)
     }
     const int nqt = (a.N + BM - 1) / BM;
     const long long total = (long long)nqt * a.B * a.H;
-    // Persistent launch for the causal kernel at d = 128: as many workgroups as the chip holds at once
-    // (one per CU: the LDS ring takes 128 KiB), each walking its share of the tile schedule.  Measured:
-    // +2.5 % on causal N = 8192 (balanced tile lengths, next prologue under the epilogue); without the
-    // mask all tiles are equally long, the hardware's own dispatch is as good and the plain launch
-    // compiles to a slightly tighter main loop, so it keeps one tile per workgroup.
+    // Persistent launch: as many workgroups as the chip holds at once (one per CU at d = 128: the LDS
+    // ring takes 128 KiB), each walking its share of the tile schedule.
     long long grid = total;
-    if (ATTN_PERSISTENT && D == 128 && CAUSAL) {
+    if (PERSIST) {
         int dev = 0, cus = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
@@ -650,8 +647,18 @@ int launch(const AttnLaunchArgs& a)
 template <int DTYPE, int D>
 int launch_d(const AttnLaunchArgs& a)
 {
-    constexpr int NW = ATTN_CFG_NW, MB = ATTN_CFG_MB, BN = ATTN_CFG_BN, STAGES = ATTN_CFG_STAGES;
-    return a.causal ? launch<DTYPE, D, NW, MB, BN, STAGES, true>(a) : launch<DTYPE, D, NW, MB, BN, STAGES, false>(a);
+    constexpr int NW = ATTN_CFG_NW, MB = D == 64 ? ATTN_CFG_MB_D64 : ATTN_CFG_MB, BN = ATTN_CFG_BN, STAGES = ATTN_CFG_STAGES;
+    // When the persistent form is used (d = 128 only: at d = 64 two workgroups share a CU and cover each
+    // other's prologue and epilogue, and the next tile's Q fragments would cost the registers that let
+    // them co-reside).  Causal: always; measured +2.5 % at N = 8192 (balanced tile lengths, next
+    // prologue under the epilogue).  Without the mask all tiles are equally long and the hardware's own
+    // dispatch balances as well; the persistent form only pays while a tile is short enough for its
+    // prologue and epilogue to matter, and its main loop compiles slightly looser (-0.3 % at N = 16384).
+    if (D == 128 && ATTN_PERSISTENT) {
+        if (a.causal) return launch<DTYPE, D, NW, MB, BN, STAGES, true, true>(a);
+        if (a.N <= ATTN_PERSIST_NC_MAX_N) return launch<DTYPE, D, NW, MB, BN, STAGES, false, true>(a);
+    }
+    return a.causal ? launch<DTYPE, D, NW, MB, BN, STAGES, true, false>(a) : launch<DTYPE, D, NW, MB, BN, STAGES, false, false>(a);
 }
 
 }  // namespace
@@ -674,7 +681,7 @@ int attn_launch_tile_param(int d, int causal, int which)
     (void)causal;
     if (d != 64 && d != 128) return -1;
     switch (which) {
-        case 0: return ATTN_CFG_NW * ATTN_CFG_MB * 32;
+        case 0: return ATTN_CFG_NW * (d == 64 ? ATTN_CFG_MB_D64 : ATTN_CFG_MB) * 32;
         case 1: return ATTN_CFG_BN;
         case 2: return ATTN_CFG_STAGES;
         case 3: return ATTN_CFG_NW * 64;

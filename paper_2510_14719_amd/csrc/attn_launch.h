@@ -6,7 +6,10 @@
 #define ATTN_CFG_NW 8        // waves per workgroup
 #endif
 #ifndef ATTN_CFG_MB
-#define ATTN_CFG_MB 1        // 32-query blocks per wave
+#define ATTN_CFG_MB 1        // 32-query blocks per wave at d = 128
+#endif
+#ifndef ATTN_CFG_MB_D64
+#define ATTN_CFG_MB_D64 1    // ... and at d = 64
 #endif
 #ifndef ATTN_CFG_BN
 #define ATTN_CFG_BN 64       // keys per K/V tile
