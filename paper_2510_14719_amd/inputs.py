@@ -113,3 +113,23 @@ def sample_rows(B: int, H: int, N: int, n: int, seed: int, always=()):
     while len(rows) < n + len(always):
         rows.add((int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(N))))
     return sorted(rows)
+
+
+# ---------------------------------------------------------------- matrix product workloads
+# The paper's matrix-multiplication sweep (Section 5.2): M = N = 8192, K from 256 to 16384, fp16; it
+# uses no dataset either, so i.i.d. N(0,1) operands of the same shapes stand in for it.
+GEMM_K_SWEEP = (256, 512, 1024, 2048, 4096, 8192, 16384)
+
+
+def make_ab(M: int, N: int, K: int, dtype: int, seed: int):
+    """A ``[M,K]`` and B ``[N,K]`` (both K-contiguous) as uint16 bit patterns; seeds ``seed, seed+1``."""
+    return normal_bits((M, K), dtype, seed), normal_bits((N, K), dtype, seed + 1)
+
+
+def sample_entries(M: int, N: int, n: int, seed: int, always=()):
+    """``n`` seeded (m, n) pairs plus the fixed ones in ``always`` (deduplicated, sorted)."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    out = {tuple(int(x) for x in r) for r in always}
+    while len(out) < n + len(always):
+        out.add((int(rng.integers(M)), int(rng.integers(N))))
+    return sorted(out)
