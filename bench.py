@@ -79,8 +79,92 @@ def mfma_sustained(binding, torch, dtype: int, stream, launches: int = 150, warm
     return out
 
 
+def gemm_cpu_baseline(M, N, K, dtype, seed, rows: int = 24) -> dict:
+    """The matrix-product oracle as it stands, timed on a few whole rows of C of the same workload."""
+    from oracle import gemm_ref
+    from paper_2510_14719_amd import inputs as I
+    gemm_ref.build()
+    rows = min(rows, M)
+    a, b = I.make_ab(rows, N, K, dtype, seed)
+    t0 = time.perf_counter()
+    gemm_ref.gemm_nt(a, b, dtype)
+    dt = time.perf_counter() - t0
+    return {"value": 2.0 * rows * N * K / dt * 1e-12, "unit": "TFLOP/s", "cores": gemm_ref.max_threads(), "kind": "oracle",
+            "seconds": dt, "sample": "%d of %d rows of C (all N=%d columns, K=%d), fp64" % (rows, M, N, K)}
+
+
+def main_gemm(args) -> int:
+    """`--op gemm`: the paper's matrix-multiplication workload, M = N = 8192, one K of its sweep."""
+    import numpy as np
+    import torch
+    from paper_2510_14719_amd import binding, inputs as I
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    binding.load_library()
+    M = N = 8192
+    K, dtype, seed = args.K, I.FP16, 7000 + args.K
+    a_bits, b_bits = I.make_ab(M, N, K, dtype, seed)
+    a = torch.from_numpy(a_bits.view("int16")).cuda()
+    b = torch.from_numpy(b_bits.view("int16")).cuda()
+    c = torch.empty((M, N), dtype=torch.int16, device="cuda")
+    stream = torch.cuda.current_stream()
+    flops = 2.0 * M * N * K
+
+    def step():
+        binding.gemm_nt(a, b, c, M, N, K, stream=stream, dtype=dtype)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record(stream)
+    for i in range(args.steps):
+        step()
+        ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_launch = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
+    ms_per_step = ev[0].elapsed_time(ev[-1]) / args.steps
+    kern_ms = statistics.fmean(per_launch)
+    achieved = flops / (kern_ms * 1e-3) * 1e-12
+    out = {
+        "metric": "matrix product C = A B^T TFLOP/s (2*M*N*K), 1 GPU", "value": flops / (ms_per_step * 1e-3) * 1e-12,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "gemm_nt: M=8192 N=8192 K=%d fp16" % K, "tile": binding.gemm_tile_params(),
+                   "flops_per_step": flops, "wall_s_timed_region": wall},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_TFLOPS[dtype], "traffic": None,
+                     "kernel_ms": {"mean": kern_ms, "median": statistics.median(per_launch), "min": min(per_launch)}},
+        "context": {"paper_h100_fp16_gemm_tflops_k16384": 718.0,
+                    "paper_workload": "H100 SXM5, M=N=8192, K=16384 (Section 5.6); other hardware, not a target"},
+    }
+    if not args.no_mfma_probe:
+        sus = mfma_sustained(binding, torch, dtype, stream)
+        sus["unit"] = "TFLOP/s"
+        sus["frac_of_random_operands"] = achieved / sus["random_operands"]
+        sus["frac_of_zero_operands"] = achieved / sus["zero_operands"]
+        out["roofline"]["mfma_only_measured"] = sus
+    if not args.no_cpu_baseline:
+        from oracle import gemm_ref
+        idx = I.sample_entries(M, N, 32, seed=seed + 5, always=[(0, 0), (M - 1, N - 1)])
+        ref = gemm_ref.gemm_nt_samples(a_bits, b_bits, dtype, idx)
+        ii = np.asarray(idx)
+        got = c.view(torch.float16)[ii[:, 0], ii[:, 1]].double().cpu().numpy()
+        out["parity_sample"] = {"entries": len(idx), "max_abs": float(np.abs(got - ref).max()),
+                                "max_rel_to_half_ulp": float((np.abs(got - ref) / (2.0 ** -11 * np.abs(ref) + 2e-6 * K)).max())}
+        out["cpu_baseline"] = gemm_cpu_baseline(M, N, K, dtype, seed)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
+    ap.add_argument("--op", default="attn", choices=["attn", "gemm"],
+                    help="attn: the headline attention workloads (default); gemm: the paper's M=N=8192 matrix product")
+    ap.add_argument("--K", type=int, default=16384, help="inner dimension of --op gemm (the paper sweeps 256 ... 16384)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=25)
@@ -97,6 +181,9 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU; the path shards over (batch, head) with no "
               "communication and no multi-GPU figure is produced (asked for --gpus %d)" % args.gpus, file=sys.stderr)
         return 2
+
+    if args.op == "gemm":
+        return main_gemm(args)
 
     import torch
     from paper_2510_14719_amd import binding, inputs as I

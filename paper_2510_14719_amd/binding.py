@@ -63,6 +63,18 @@ def load_library() -> ctypes.CDLL:
         lib.attn_fwd_mfma_probe_flops.argtypes = [ci, ci]
         lib.attn_fwd_mfma_probe_sink_floats.restype = ci
         lib.attn_fwd_mfma_probe_sink_floats.argtypes = [ci]
+        lib.gemm_nt.restype = ci
+        lib.gemm_nt.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci]
+        lib.gemm_nt_f16.restype = ci
+        lib.gemm_nt_f16.argtypes = [vp, vp, vp, ci, ci, ci, vp]
+        lib.gemm_nt_bf16.restype = ci
+        lib.gemm_nt_bf16.argtypes = [vp, vp, vp, ci, ci, ci, vp]
+        lib.gemm_nt_check_args.restype = ci
+        lib.gemm_nt_check_args.argtypes = [vp, vp, vp, ci, ci, ci, ci]
+        lib.gemm_nt_strerror.restype = ctypes.c_char_p
+        lib.gemm_nt_strerror.argtypes = [ci]
+        lib.gemm_nt_tile_param.restype = ci
+        lib.gemm_nt_tile_param.argtypes = [ci]
         _lib = lib
     return _lib
 
@@ -148,3 +160,39 @@ def mfma_probe(sink, workgroups: int, iters: int, random_operands: bool, dtype: 
     if rc != 0:
         raise AttnFwdError(rc, strerror(rc))
     return float(lib.attn_fwd_mfma_probe_flops(int(workgroups), int(iters)))
+
+
+class GemmNtError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("gemm_nt failed with code %d: %s" % (code, text))
+        self.code = code
+
+
+def gemm_nt_raw(a, b, c, M, N, K, stream, dtype) -> int:
+    """The C call itself; returns its code without raising."""
+    return int(load_library().gemm_nt(_ptr(a), _ptr(b), _ptr(c), int(M), int(N), int(K), _stream_handle(stream), int(dtype)))
+
+
+def gemm_nt(a, b, c, M, N, K, stream=None, dtype=None) -> None:
+    """``gemm_nt(a, b, c, M, N, K, stream, dtype)`` of the C ABI: ``C = A B^T`` for ``a`` [M,K], ``b`` [N,K].
+
+    ``dtype`` defaults to the element type of ``a``.  Asynchronous: the kernel is enqueued on
+    ``stream`` (default: torch's current stream) and the call returns.
+    """
+    if dtype is None:
+        import torch
+        if a.dtype == torch.float16:
+            dtype = FP16
+        elif a.dtype == torch.bfloat16:
+            dtype = BF16
+        else:
+            raise ValueError("pass dtype=FP16/BF16 for tensors of type %s" % a.dtype)
+    rc = gemm_nt_raw(a, b, c, M, N, K, stream, dtype)
+    if rc != 0:
+        raise GemmNtError(rc, load_library().gemm_nt_strerror(rc).decode())
+
+
+def gemm_tile_params() -> dict:
+    lib = load_library()
+    return {"BM": lib.gemm_nt_tile_param(0), "BN": lib.gemm_nt_tile_param(1), "BK": lib.gemm_nt_tile_param(2),
+            "stages": lib.gemm_nt_tile_param(3), "threads": lib.gemm_nt_tile_param(4)}

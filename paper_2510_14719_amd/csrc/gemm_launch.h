@@ -1,0 +1,17 @@
+// Internal seam between the host-side C ABI (gemm_api.cpp) and the kernel (gemm_nt_kernel.hip).
+#pragma once
+
+struct GemmLaunchArgs {
+    const void* a;   // [M][K]
+    const void* b;   // [N][K]
+    void* c;         // [M][N]
+    int M, N, K;
+    int dtype;       // 0 = fp16, 1 = bf16
+    void* stream;    // hipStream_t
+};
+
+// Enqueue the kernel for already-validated arguments.  0 on success, -1 if HIP refused the launch.
+int gemm_launch(const GemmLaunchArgs& a);
+
+// Rows of C per workgroup (0), columns (1), K tile (2), LDS stages (3), threads per workgroup (4).
+int gemm_launch_tile_param(int which);

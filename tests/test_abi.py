@@ -8,6 +8,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "attn_fwd.h")
+GEMM_HEADER = os.path.join(ROOT, "include", "gemm_nt.h")
 
 
 @pytest.fixture(scope="module")
@@ -87,3 +88,38 @@ def test_mfma_probe_validation_needs_no_gpu(lib):
     # 8 waves x iters x 8 MFMAs x 2*32*32*16 flops per workgroup
     assert lib.attn_fwd_mfma_probe_flops(2, 10) == 2 * 8 * 10 * 8 * 32768.0
     assert lib.attn_fwd_mfma_probe_flops(0, 10) == 0.0
+
+
+def test_gemm_header_symbols_are_exported(lib):
+    src = re.sub(r"/\*.*?\*/", "", open(GEMM_HEADER).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(gemm_nt\w*)\s*\(", src)))
+    assert {"gemm_nt", "gemm_nt_f16", "gemm_nt_bf16", "gemm_nt_check_args", "gemm_nt_strerror", "gemm_nt_tile_param"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), "library does not export %s" % n
+
+
+def test_gemm_argument_validation_needs_no_gpu(lib):
+    a, b, c = 0x10000000, 0x20000000, 0x30000000
+    f = lib.gemm_nt_check_args
+    assert f(a, b, c, 256, 256, 64, 0) == 0
+    assert f(a, b, c, 1, 1, 32, 1) == 0
+    assert f(0, b, c, 256, 256, 64, 0) == -1
+    assert f(a, b, 0, 256, 256, 64, 0) == -1
+    assert f(a, b, c, 0, 256, 64, 0) == -2
+    assert f(a, b, c, 256, 0, 64, 0) == -2
+    assert f(a, b, c, 256, 256, 0, 0) == -2
+    assert f(a, b, c, 256, 256, 48, 0) == -2          # K must be a multiple of 32
+    assert f(a, b, c, 256, 256, 64, 2) == -2
+    assert f(a + 8, b, c, 256, 256, 64, 0) == -4
+    assert f(a, b, c + 1, 256, 256, 64, 0) == -4
+    assert f(a, b, c, 65536, 256, 16384, 0) == -5     # 2 GiB of A
+    assert f(a, b, a, 256, 256, 64, 0) == -7
+    assert f(a, b, b + 64, 256, 256, 64, 0) == -7
+    # the entry points run the same validation first
+    assert lib.gemm_nt(None, None, None, 1, 1, 32, None, 0) == -1
+    assert lib.gemm_nt_f16(a, b, c, 8, 8, 31, None) == -2
+    assert lib.gemm_nt_bf16(a, b, c, 8, 8, 64 + 8, None) == -2
+    for code in range(-8, 1):
+        assert len(lib.gemm_nt_strerror(code)) > 3
+    bm, bn, bk, st, th = (lib.gemm_nt_tile_param(w) for w in range(5))
+    assert st * (bm + bn) * bk * 2 <= 160 * 1024 and th % 64 == 0 and lib.gemm_nt_tile_param(9) == -1
