@@ -13,12 +13,20 @@
 // lane ends up with one row m of C and runs of four consecutive n: the 16-bit results leave as 8-byte
 // stores (computed the other way round a lane would hold single elements of 16 different rows).
 //
-// Schedule of one wave, K tile j (32 wide, two MFMA k-steps):
+// Schedule of one wave, K tile j (32 wide, two MFMA k-steps, 16 MFMAs):
 //   wait for its own copies of stage j+1; barrier (everyone's stage j+1 is complete, nobody reads
-//   stage j-1 any more); issue the copies of stage j+3 into the slot of j-1;
-//   request the k-step-1 fragments of tile j; 8 MFMAs on the k-step-0 fragments, which were
-//   requested during tile j-1 (stage j was already complete then) -- so the matrix core has work
-//   the moment the barrier opens; request the k-step-0 fragments of tile j+1; 8 MFMAs on k-step 1.
+//   stage j-1 any more, so its slot takes the copies of stage j+3); then 16 MFMAs on fragments that
+//   were requested during tile j-1, with one LDS request (a fragment of tile j+1) or one copy (of
+//   stage j+3) issued after each MFMA.
+//
+// Measured on the device (M = N = 8192, K = 8192, fp16 N(0,1) operands, same box and session):
+//   this kernel 1.16 PFLOP/s; with the copies left out (wrong results, timing only) 1.40; with the
+//   fragment reads left out 1.23; with neither 1.60, which is the chip's random-operand MFMA-only
+//   rate.  Copies always taken from the same K tile (L2 hits only): no change, so the memory side is
+//   not the limit.  Four extra producer waves that do all the copying (warp specialisation as in the
+//   paper): slower, 1.00.  Four waves of 128 x 128 instead of eight of 128 x 64 (a third fewer LDS
+//   reads, accumulators in AGPRs): the same, 1.09-1.16.  A fifth ring stage: the same.  Lanes of a copy
+//   mapped to rows (lane -> row L%16) instead of to the 16-byte columns of a row: 0.96.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -28,17 +36,47 @@
 
 namespace {
 
-constexpr int G_NW = 8;                 // waves per workgroup
+#ifdef GEMM_TIMING
+// Profiling builds only: per-wave cycle totals of the main-loop sections of the first workgroups.
+__device__ unsigned long long gemm_dbg[256 * 8 * 8];
+#define GSTAMP(var) unsigned long long var; __builtin_amdgcn_sched_barrier(0); \
+    asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(var) :: "memory"); __builtin_amdgcn_sched_barrier(0)
+#define GACC(slot, a, b) dbg_acc[slot] += (b) - (a)
+#else
+#define GSTAMP(var)
+#define GACC(slot, a, b)
+#endif
+
+// Producer waves: 0 = every wave copies and computes; 4 = one extra wave per SIMD does all the copying
+// (the paper's warp specialisation, Section 3.2: a producer role feeding the consumers through the ring).
+#ifndef GEMM_PRODUCERS
+#define GEMM_PRODUCERS 0
+#endif
+#ifndef GEMM_COMPUTE_WAVES
+#define GEMM_COMPUTE_WAVES 8
+#endif
+constexpr int G_CW = GEMM_COMPUTE_WAVES; // computing waves per workgroup: 8 (two per SIMD, 128 x 64 of C each) or 4 (one per SIMD, 128 x 128)
+constexpr int G_NB = 8 / (G_CW / 2);    // 32-column blocks of C per wave (the wave's rows are always 4 blocks)
+static_assert(G_CW == 8 || G_CW == 4, "wave layout is 2 x (G_CW / 2)");
+constexpr int G_PW = GEMM_PRODUCERS;    // producer waves
+constexpr int G_NW = G_CW + G_PW;       // waves per workgroup
+constexpr int G_COPIERS = G_PW > 0 ? G_PW : G_CW;
 constexpr int G_BM = 256, G_BN = 256;   // tile of C per workgroup
 constexpr int G_BK = 32;                // K tile
-constexpr int G_STAGES = 4;
+#ifndef GEMM_STAGES
+#define GEMM_STAGES 4
+#endif
+constexpr int G_STAGES = GEMM_STAGES;   // ring depth: 4 (128 KiB) or 5 (all 160 KiB of the LDS)
+constexpr int G_AHEAD = G_STAGES - 1;   // copies run this many K tiles ahead of the tile being multiplied
+static_assert(G_STAGES == 4 || G_STAGES == 5, "ring protocol below");
 constexpr int G_OPER_BYTES = G_BM * G_BK * 2;        // one operand tile in the LDS (16 KiB)
 constexpr int G_STAGE_BYTES = 2 * G_OPER_BYTES;      // A tile, then B tile
 constexpr int G_PIECES = G_OPER_BYTES / 1024;        // 1 KiB wave-transfers per operand tile (16 rows x 64 B each)
-constexpr int G_PPW = G_PIECES / G_NW;               // ... per wave and operand
+constexpr int G_PPW = G_PIECES / G_COPIERS;          // ... per copying wave and operand
 constexpr int G_LPG = 2 * G_PPW;                     // copies a wave issues per stage
 constexpr int G_GROUP_M = 8;                         // tile rows per raster group (see tile_coords)
-static_assert(G_BM == G_BN && G_PIECES % G_NW == 0, "operand tiles are copied the same way");
+static_assert(G_BM == G_BN && G_PIECES % G_COPIERS == 0, "operand tiles are copied the same way");
+static_assert(3 * G_LPG <= 63, "the stages in flight must fit the vmcnt counter");
 
 // Logical tile -> (tile row, tile column): tile rows are taken in groups of G_GROUP_M and a group is
 // walked column by column, so tiles that run at the same time share A row panels and B row panels
@@ -64,7 +102,9 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int lr = lane & 31, g = lane >> 5;
-    const int wm = wave & 1, wn = wave >> 1;                 // the wave's 128 x 64 block inside the tile
+    const int wm = wave & 1, wn = (wave >> 1) & (G_CW / 2 - 1);   // the wave's 128 x (32 G_NB) block inside the tile
+    const bool copier = G_PW > 0 ? wave >= G_CW : true;      // does this wave issue copies
+    const int cwave = G_PW > 0 ? wave - G_CW : wave;         // ... and its index among those that do
 
     int tm, tn;
     tile_coords(__builtin_amdgcn_readfirstlane(tile_schedule(ntm * ntn, (int)gridDim.x, (int)blockIdx.x, 0)), ntm, ntn, tm, tn);
@@ -72,18 +112,24 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
     const int nk = K / G_BK;
     const size_t row_bytes = (size_t)K * 2;
 
-    // ---- global -> LDS copies.  Operand tile in the LDS: [16-row block][16-byte column (4)][row (16)][16 B];
-    // one copy instruction moves a 16-row block: lane L fetches row L%16, column L/16 (LDS offset 16*L).
+    // ---- global -> LDS copies.  One copy instruction moves a 16-row block of an operand tile (16 rows x
+    // 64 B = 1 KiB) and lane L's 16 bytes land at LDS offset 16*L, so the lane -> address map fixes the
+    // LDS layout.  Lanes 4r..4r+3 fetch the four 16-byte columns of row r: only neighbouring lanes are
+    // merged into one 64-byte request on the way to the L2 (measured: 29 TB/s chip-wide against 9.5 with
+    // lane -> row L%16).  The block is therefore row-major in the LDS, 64 B per row, which alone would
+    // put rows r and r+4 on the same banks for the fragment reads below; the columns of row r are
+    // stored rotated by (r/4)%4 (lane L fetches column (L%4) ^ ((L/16)%4)), which makes them conflict free.
     // Inside the matrix the per-lane offset is a constant and the piece / K-tile offset sits in the scalar
     // base; tiles that overhang the matrix clamp their rows (the surplus rows are never stored).
     const bool interior = m0 + G_BM <= M && n0 + G_BN <= N;
-    const unsigned lane_off = (unsigned)((lane & 15) * row_bytes) + (lane >> 4) * 16;
+    const int lane_row = lane >> 2, lane_col = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;
+    const unsigned lane_off = (unsigned)(lane_row * row_bytes) + lane_col;
     const char* a_piece[G_PPW];
     const char* b_piece[G_PPW];
     unsigned a_voff[G_PPW], b_voff[G_PPW];
 #pragma unroll
     for (int i = 0; i < G_PPW; ++i) {
-        const int p = wave * G_PPW + i;
+        const int p = (copier ? cwave : 0) * G_PPW + i;
         if (interior) {
             a_piece[i] = reinterpret_cast<const char*>(A) + (size_t)(m0 + p * 16) * row_bytes;
             b_piece[i] = reinterpret_cast<const char*>(B) + (size_t)(n0 + p * 16) * row_bytes;
@@ -91,74 +137,146 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
         } else {
             a_piece[i] = reinterpret_cast<const char*>(A);
             b_piece[i] = reinterpret_cast<const char*>(B);
-            a_voff[i] = (unsigned)((size_t)min(m0 + p * 16 + (lane & 15), M - 1) * row_bytes) + (lane >> 4) * 16;
-            b_voff[i] = (unsigned)((size_t)min(n0 + p * 16 + (lane & 15), N - 1) * row_bytes) + (lane >> 4) * 16;
+            a_voff[i] = (unsigned)((size_t)min(m0 + p * 16 + lane_row, M - 1) * row_bytes) + lane_col;
+            b_voff[i] = (unsigned)((size_t)min(n0 + p * 16 + lane_row, N - 1) * row_bytes) + lane_col;
         }
     }
-    auto issue_stage = [&](int s) __attribute__((always_inline)) {
-        const unsigned sbase = lds_base + (s % G_STAGES) * G_STAGE_BYTES + wave * (G_PPW * 1024);
+    // One copy of stage s: piece i < G_PPW of the A tile, else piece i - G_PPW of the B tile.
+    auto issue_piece = [&](int s, int i) __attribute__((always_inline)) {
+        const unsigned sbase = lds_base + (s % G_STAGES) * G_STAGE_BYTES + cwave * (G_PPW * 1024);
         const size_t koff = (size_t)s * (G_BK * 2);
+        if (i < G_PPW) dma16(a_piece[i] + koff, a_voff[i], sbase + i * 1024);
+        else dma16(b_piece[i - G_PPW] + koff, b_voff[i - G_PPW], sbase + G_OPER_BYTES + (i - G_PPW) * 1024);
+    };
+    auto issue_stage = [&](int s) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < G_PPW; ++i) dma16(a_piece[i] + koff, a_voff[i], sbase + i * 1024);
-#pragma unroll
-        for (int i = 0; i < G_PPW; ++i) dma16(b_piece[i] + koff, b_voff[i], sbase + G_OPER_BYTES + i * 1024);
+        for (int i = 0; i < G_LPG; ++i) issue_piece(s, i);
     };
 
     // ---- fragments: 32 rows x 16 k of an operand tile; lane l holds row l%32, k = 16*ks + 8*(l/32) .. +7
-    const int frag_lane = (lr >> 4) * 1024 + g * 256 + (lr & 15) * 16;
-    struct Frags { s16x8 bn[2]; s16x8 am[4]; };        // B-matrix rows (n) feed the MFMA's A operand, A-matrix rows (m) its B operand
-    auto read_frags = [&](int s, int ks) __attribute__((always_inline)) -> Frags {
-        const char* st = smem + (s % G_STAGES) * G_STAGE_BYTES + frag_lane + ks * 512;
-        Frags f;
+    // (row lr%16 of 16-row block lr/16; 16-byte column 2*ks + g, stored at position column ^ ((row/4)%4))
+    int frag_lane[2];
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-            f.bn[nb] = *reinterpret_cast<const s16x8*>(st + G_OPER_BYTES + (wn * 2 + nb) * 2048);
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-            f.am[mb] = *reinterpret_cast<const s16x8*>(st + (wm * 4 + mb) * 2048);
-        return f;
+    for (int ks = 0; ks < 2; ++ks)
+        frag_lane[ks] = (lr >> 4) * 1024 + (lr & 15) * 64 + (((ks * 2 + g) ^ ((lr >> 2) & 3)) * 16);
+    // B-matrix rows (n) feed the MFMA's A operand, A-matrix rows (m) its B operand.
+    auto read_bn = [&](int s, int ks, int nb) __attribute__((always_inline)) -> s16x8 {
+        return *reinterpret_cast<const s16x8*>(smem + (s % G_STAGES) * G_STAGE_BYTES + frag_lane[ks] + G_OPER_BYTES + (wn * G_NB + nb) * 2048);
+    };
+    auto read_am = [&](int s, int ks, int mb) __attribute__((always_inline)) -> s16x8 {
+        return *reinterpret_cast<const s16x8*>(smem + (s % G_STAGES) * G_STAGE_BYTES + frag_lane[ks] + (wm * 4 + mb) * 2048);
     };
 
-    f32x16 acc[2][4];
+    f32x16 acc[G_NB][4];
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < G_NB; ++nb)
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = f32x16(0.f);
-    auto mfmas = [&](const Frags& f) __attribute__((always_inline)) {
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) acc[nb][mb] = E::mfma(f.bn[nb], f.am[mb], acc[nb][mb]);
+    // All fragments of one K tile of this wave: 2 k-steps x (G_NB B-matrix + 4 A-matrix fragments).
+    struct TileFrags { s16x8 bn[2][G_NB]; s16x8 am[2][4]; };
+    constexpr int FRAGS_PER_TILE = 2 * (G_NB + 4), MFMAS_PER_TILE = 8 * G_NB;
+    // Fragment number i of a tile, in the order the MFMAs need them.
+    auto read_frag = [&](TileFrags& t, int s, int i) __attribute__((always_inline)) {
+        const int ks = i / (G_NB + 4), r = i % (G_NB + 4);
+        if (r < G_NB) t.bn[ks][r] = read_bn(s, ks, r);
+        else t.am[ks][r - G_NB] = read_am(s, ks, r - G_NB);
+    };
+    static_assert(G_PW > 0 || FRAGS_PER_TILE + G_LPG <= MFMAS_PER_TILE, "one request or copy per MFMA slot");
+
+    // Own copies of stage j+1 complete: only the stages after it (at most G_AHEAD - 2 of them) stay in flight.
+    auto wait_next_stage = [&](int j) __attribute__((always_inline)) {
+        if (G_AHEAD > 3 && j + 3 < nk) wait_vmcnt<2 * G_LPG>();
+        else if (j + 2 < nk) wait_vmcnt<G_LPG>();
+        else wait_vmcnt<0>();
     };
 
-    // ---- prologue: three stages in flight; stage 0 complete for everyone; first fragments requested
-    issue_stage(0);
-    if (nk > 1) issue_stage(1);
-    if (nk > 2) issue_stage(2);
-    if (nk > 2) wait_vmcnt<2 * G_LPG>(); else if (nk > 1) wait_vmcnt<G_LPG>(); else wait_vmcnt<0>();
+    // ---- prologue: G_AHEAD stages in flight; stage 0 complete for everyone; first fragments requested
+    if (copier) {
+        issue_stage(0);
+        if (nk > 1) issue_stage(1);
+        if (nk > 2) issue_stage(2);
+        if (G_AHEAD > 3 && nk > 3) issue_stage(3);
+        // stage 0 must be complete: everything but the later stages' copies
+        if (G_AHEAD > 3 && nk > 3) wait_vmcnt<3 * G_LPG>();
+        else if (nk > 2) wait_vmcnt<2 * G_LPG>(); else if (nk > 1) wait_vmcnt<G_LPG>(); else wait_vmcnt<0>();
+    }
     __builtin_amdgcn_s_barrier();
-    Frags f0 = read_frags(0, 0);
-    __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): same state on both ways into the loop (see its end)
-
-    // (bottom-tested: with the exit test at the top the accumulators would be copied every iteration)
-    int j = 0;
-    do {
-        if (j + 2 < nk) wait_vmcnt<G_LPG>(); else wait_vmcnt<0>();
+    if (G_PW > 0 && copier) {
+        // producer: keeps the ring three stages ahead; one barrier per K tile like everyone else
+        for (int j = 0; j < nk; ++j) {
+            wait_next_stage(j);
+            __builtin_amdgcn_s_barrier();
+            if (j + G_AHEAD < nk) issue_stage(j + G_AHEAD);
+        }
+        return;
+    }
+    // One K tile: multiply from the fragments in `cur` (requested during the previous tile) and request
+    // the next tile's fragments into `nxt`, one request after each MFMA: with the copies' writes the LDS
+    // is close to saturated and a request can take hundreds of cycles, so every fragment gets a whole
+    // tile (16 MFMAs per wave, 32 per SIMD) to arrive.  Stage j+1 is complete at barrier j, which is what
+    // makes the early requests legal, and the matrix core has work the moment the barrier opens.  When
+    // every wave copies, the copies of the stage three tiles ahead go out in the remaining MFMA slots,
+    // evenly spread: a wave queueing for the CU's copy path cannot issue its MFMAs meanwhile.
+#ifdef GEMM_TIMING
+    unsigned long long dbg_acc[8] = {};
+    const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime(), ct0 = __builtin_readcyclecounter();
+#endif
+    auto tile = [&](int j, const TileFrags& cur, TileFrags& nxt) __attribute__((always_inline)) {
+        GSTAMP(t0);
+        if (G_PW == 0) wait_next_stage(j);
+        GSTAMP(t1);
         __builtin_amdgcn_s_barrier();
-        if (j + 3 < nk) issue_stage(j + 3);
-        const Frags f1 = read_frags(j, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(f0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (j + 1 < nk) f0 = read_frags(j + 1, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(f1);
-        __builtin_amdgcn_sched_barrier(0);
-        // The next tile's first fragments have landed long ago; saying so here keeps the compiler from
-        // waiting for ALL outstanding LDS reads (the fresh k-step-1 requests included) at the loop top.
+        GSTAMP(t2);
+        const int cs = G_PW == 0 && j + G_AHEAD < nk ? j + G_AHEAD : -1;   // the stage whose copies go out during this tile
+        const int jn = j + 1 < nk ? j + 1 : j;                             // (the last tile re-reads itself: harmless, unused)
+        constexpr int COPY_EVERY = G_PW == 0 ? MFMAS_PER_TILE / G_LPG : MFMAS_PER_TILE + 1;
+        int next_frag = 0;
+#pragma unroll
+        for (int q = 0; q < MFMAS_PER_TILE; ++q) {
+            const int ks = q / (4 * G_NB), mb = (q / G_NB) % 4, nb = q % G_NB;
+            acc[nb][mb] = E::mfma(cur.bn[ks][nb], cur.am[ks][mb], acc[nb][mb]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (q % COPY_EVERY == COPY_EVERY - 1) {
+                if (cs >= 0) issue_piece(cs, q / COPY_EVERY);
+            } else if (next_frag < FRAGS_PER_TILE) {
+                read_frag(nxt, jn, next_frag);
+                ++next_frag;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        GSTAMP(t5);
+        GACC(0, t0, t1); GACC(1, t1, t2); GACC(4, t2, t5);
+        // Everything requested above has to be in its registers before the next tile uses it; waiting here,
+        // after the last MFMA was issued, costs nothing and keeps the compiler from inserting a wait for
+        // ALL outstanding requests in the middle of the next tile.
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
-    } while (++j < nk);
+    };
 
+    TileFrags X, Y;
+#pragma unroll
+    for (int i = 0; i < FRAGS_PER_TILE; ++i) read_frag(X, 0, i);
+    __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
+    // Tiles are taken in pairs so that the two fragment sets swap roles without a register copy; the
+    // loop is bottom-tested (with the exit test at the top the accumulators would be copied every
+    // iteration) and an odd last tile is peeled off.
+    int j = 0;
+    if (nk >= 2) {
+        do {
+            tile(j, X, Y);
+            tile(j + 1, Y, X);
+            j += 2;
+        } while (j + 1 < nk);
+    }
+    if (j < nk) tile(j, X, Y);
+
+#ifdef GEMM_TIMING
+    if (blockIdx.x < 256 && lane == 0) {
+        dbg_acc[5] = nk;
+        dbg_acc[6] = __builtin_amdgcn_s_memrealtime() - rt0;
+        dbg_acc[7] = __builtin_readcyclecounter() - ct0;
+        for (int i = 0; i < 8; ++i) gemm_dbg[(blockIdx.x * 8 + wave) * 8 + i] = dbg_acc[i];
+    }
+#endif
     // ---- epilogue: lane holds row m of C and, per accumulator register quad, four consecutive n
     const bool vec_ok = (N & 3) == 0 && (reinterpret_cast<uintptr_t>(C) & 7) == 0;
 #pragma unroll
@@ -167,10 +285,10 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
         if (m >= M) continue;
         uint16_t* crow = C + (size_t)m * N;
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < G_NB; ++nb)
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
-                const int n = n0 + wn * 64 + nb * 32 + i4 * 8 + g * 4;
+                const int n = n0 + wn * (G_NB * 32) + nb * 32 + i4 * 8 + g * 4;
                 u32x2 w;
                 w[0] = E::pack2(acc[nb][mb][i4 * 4 + 0], acc[nb][mb][i4 * 4 + 1]);
                 w[1] = E::pack2(acc[nb][mb][i4 * 4 + 2], acc[nb][mb][i4 * 4 + 3]);
@@ -208,6 +326,13 @@ int launch(const GemmLaunchArgs& a)
 }
 
 }  // namespace
+
+#ifdef GEMM_TIMING
+extern "C" int gemm_dbg_read(unsigned long long* host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(gemm_dbg), sizeof(unsigned long long) * n);
+}
+#endif
 
 int gemm_launch(const GemmLaunchArgs& a) { return a.dtype == 0 ? launch<0>(a) : launch<1>(a); }
 
