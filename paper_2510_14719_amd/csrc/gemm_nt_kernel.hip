@@ -24,7 +24,8 @@
 //   fragment reads left out 1.23; with neither 1.60, which is the chip's random-operand MFMA-only
 //   rate.  Copies always taken from the same K tile (L2 hits only): no change, so the memory side is
 //   not the limit.  Four extra producer waves that do all the copying (warp specialisation as in the
-//   paper): slower, 1.00.  Four waves of 128 x 128 instead of eight of 128 x 64 (a third fewer LDS
+//   paper; tried with a leaner fragment schedule that fits the 168 registers of three waves per SIMD):
+//   slower, 1.00.  Four waves of 128 x 128 instead of eight of 128 x 64 (a third fewer LDS
 //   reads, accumulators in AGPRs): the same, 1.09-1.16.  A fifth ring stage: the same.  Lanes of a copy
 //   mapped to rows (lane -> row L%16) instead of to the 16-byte columns of a row: 0.96.
 #include <hip/hip_runtime.h>
@@ -47,20 +48,14 @@ __device__ unsigned long long gemm_dbg[256 * 8 * 8];
 #define GACC(slot, a, b)
 #endif
 
-// Producer waves: 0 = every wave copies and computes; 4 = one extra wave per SIMD does all the copying
-// (the paper's warp specialisation, Section 3.2: a producer role feeding the consumers through the ring).
-#ifndef GEMM_PRODUCERS
-#define GEMM_PRODUCERS 0
-#endif
 #ifndef GEMM_COMPUTE_WAVES
 #define GEMM_COMPUTE_WAVES 8
 #endif
 constexpr int G_CW = GEMM_COMPUTE_WAVES; // computing waves per workgroup: 8 (two per SIMD, 128 x 64 of C each) or 4 (one per SIMD, 128 x 128)
 constexpr int G_NB = 8 / (G_CW / 2);    // 32-column blocks of C per wave (the wave's rows are always 4 blocks)
 static_assert(G_CW == 8 || G_CW == 4, "wave layout is 2 x (G_CW / 2)");
-constexpr int G_PW = GEMM_PRODUCERS;    // producer waves
-constexpr int G_NW = G_CW + G_PW;       // waves per workgroup
-constexpr int G_COPIERS = G_PW > 0 ? G_PW : G_CW;
+constexpr int G_NW = G_CW;              // waves per workgroup (every wave copies and computes)
+constexpr int G_COPIERS = G_CW;
 constexpr int G_BM = 256, G_BN = 256;   // tile of C per workgroup
 constexpr int G_BK = 32;                // K tile
 #ifndef GEMM_STAGES
@@ -103,8 +98,6 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
     const int lane = threadIdx.x & 63;
     const int lr = lane & 31, g = lane >> 5;
     const int wm = wave & 1, wn = (wave >> 1) & (G_CW / 2 - 1);   // the wave's 128 x (32 G_NB) block inside the tile
-    const bool copier = G_PW > 0 ? wave >= G_CW : true;      // does this wave issue copies
-    const int cwave = G_PW > 0 ? wave - G_CW : wave;         // ... and its index among those that do
 
     int tm, tn;
     tile_coords(__builtin_amdgcn_readfirstlane(tile_schedule(ntm * ntn, (int)gridDim.x, (int)blockIdx.x, 0)), ntm, ntn, tm, tn);
@@ -129,7 +122,7 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
     unsigned a_voff[G_PPW], b_voff[G_PPW];
 #pragma unroll
     for (int i = 0; i < G_PPW; ++i) {
-        const int p = (copier ? cwave : 0) * G_PPW + i;
+        const int p = wave * G_PPW + i;
         if (interior) {
             a_piece[i] = reinterpret_cast<const char*>(A) + (size_t)(m0 + p * 16) * row_bytes;
             b_piece[i] = reinterpret_cast<const char*>(B) + (size_t)(n0 + p * 16) * row_bytes;
@@ -143,7 +136,7 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
     }
     // One copy of stage s: piece i < G_PPW of the A tile, else piece i - G_PPW of the B tile.
     auto issue_piece = [&](int s, int i) __attribute__((always_inline)) {
-        const unsigned sbase = lds_base + (s % G_STAGES) * G_STAGE_BYTES + cwave * (G_PPW * 1024);
+        const unsigned sbase = lds_base + (s % G_STAGES) * G_STAGE_BYTES + wave * (G_PPW * 1024);
         const size_t koff = (size_t)s * (G_BK * 2);
         if (i < G_PPW) dma16(a_piece[i] + koff, a_voff[i], sbase + i * 1024);
         else dma16(b_piece[i - G_PPW] + koff, b_voff[i - G_PPW], sbase + G_OPER_BYTES + (i - G_PPW) * 1024);
@@ -181,7 +174,7 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
         if (r < G_NB) t.bn[ks][r] = read_bn(s, ks, r);
         else t.am[ks][r - G_NB] = read_am(s, ks, r - G_NB);
     };
-    static_assert(G_PW > 0 || FRAGS_PER_TILE + G_LPG <= MFMAS_PER_TILE, "one request or copy per MFMA slot");
+    static_assert(FRAGS_PER_TILE + G_LPG <= MFMAS_PER_TILE, "one request or copy per MFMA slot");
 
     // Own copies of stage j+1 complete: only the stages after it (at most G_AHEAD - 2 of them) stay in flight.
     auto wait_next_stage = [&](int j) __attribute__((always_inline)) {
@@ -191,25 +184,15 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
     };
 
     // ---- prologue: G_AHEAD stages in flight; stage 0 complete for everyone; first fragments requested
-    if (copier) {
-        issue_stage(0);
-        if (nk > 1) issue_stage(1);
-        if (nk > 2) issue_stage(2);
-        if (G_AHEAD > 3 && nk > 3) issue_stage(3);
-        // stage 0 must be complete: everything but the later stages' copies
-        if (G_AHEAD > 3 && nk > 3) wait_vmcnt<3 * G_LPG>();
-        else if (nk > 2) wait_vmcnt<2 * G_LPG>(); else if (nk > 1) wait_vmcnt<G_LPG>(); else wait_vmcnt<0>();
-    }
+    issue_stage(0);
+    if (nk > 1) issue_stage(1);
+    if (nk > 2) issue_stage(2);
+    if (G_AHEAD > 3 && nk > 3) issue_stage(3);
+    // stage 0 must be complete: everything but the later stages' copies
+    if (G_AHEAD > 3 && nk > 3) wait_vmcnt<3 * G_LPG>();
+    else if (nk > 2) wait_vmcnt<2 * G_LPG>(); else if (nk > 1) wait_vmcnt<G_LPG>(); else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (G_PW > 0 && copier) {
-        // producer: keeps the ring three stages ahead; one barrier per K tile like everyone else
-        for (int j = 0; j < nk; ++j) {
-            wait_next_stage(j);
-            __builtin_amdgcn_s_barrier();
-            if (j + G_AHEAD < nk) issue_stage(j + G_AHEAD);
-        }
-        return;
-    }
+
     // One K tile: multiply from the fragments in `cur` (requested during the previous tile) and request
     // the next tile's fragments into `nxt`, one request after each MFMA: with the copies' writes the LDS
     // is close to saturated and a request can take hundreds of cycles, so every fragment gets a whole
@@ -223,13 +206,13 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
 #endif
     auto tile = [&](int j, const TileFrags& cur, TileFrags& nxt) __attribute__((always_inline)) {
         GSTAMP(t0);
-        if (G_PW == 0) wait_next_stage(j);
+        wait_next_stage(j);
         GSTAMP(t1);
         __builtin_amdgcn_s_barrier();
         GSTAMP(t2);
-        const int cs = G_PW == 0 && j + G_AHEAD < nk ? j + G_AHEAD : -1;   // the stage whose copies go out during this tile
+        const int cs = j + G_AHEAD < nk ? j + G_AHEAD : -1;   // the stage whose copies go out during this tile
         const int jn = j + 1 < nk ? j + 1 : j;                             // (the last tile re-reads itself: harmless, unused)
-        constexpr int COPY_EVERY = G_PW == 0 ? MFMAS_PER_TILE / G_LPG : MFMAS_PER_TILE + 1;
+        constexpr int COPY_EVERY = MFMAS_PER_TILE / G_LPG;
         int next_frag = 0;
 #pragma unroll
         for (int q = 0; q < MFMAS_PER_TILE; ++q) {
