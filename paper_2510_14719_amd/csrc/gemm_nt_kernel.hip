@@ -48,6 +48,10 @@ __device__ unsigned long long gemm_dbg[256 * 8 * 8];
 #define GACC(slot, a, b)
 #endif
 
+// LDS requests of a tile that may still be outstanding when the next tile starts (see the end of `tile`).
+#ifndef GEMM_TAIL_READS
+#define GEMM_TAIL_READS 3
+#endif
 #ifndef GEMM_COMPUTE_WAVES
 #define GEMM_COMPUTE_WAVES 8
 #endif
@@ -229,10 +233,11 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
         }
         GSTAMP(t5);
         GACC(0, t0, t1); GACC(1, t1, t2); GACC(4, t2, t5);
-        // Everything requested above has to be in its registers before the next tile uses it; waiting here,
-        // after the last MFMA was issued, costs nothing and keeps the compiler from inserting a wait for
-        // ALL outstanding requests in the middle of the next tile.
-        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+        // The fragments the next tile needs first were requested first and have landed; the last few
+        // requests may still be in flight (their MFMAs come late in the next tile).  Saying so here, instead
+        // of nothing, keeps the compiler from waiting for ALL outstanding requests at the loop top, and
+        // waiting for all of them would stall every tile by an LDS latency.
+        __builtin_amdgcn_s_waitcnt(0xC07F | (GEMM_TAIL_READS << 8));   // lgkmcnt(GEMM_TAIL_READS)
     };
 
     TileFrags X, Y;
