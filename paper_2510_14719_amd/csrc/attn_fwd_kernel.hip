@@ -44,7 +44,7 @@ constexpr float RESCALE_LOG2 = 8.0f;
 
 // LDS fragments requested ahead of their MFMA inside a burst (see mfma_burst).
 #ifndef ATTN_FWIN
-#define ATTN_FWIN 4
+#define ATTN_FWIN 2
 #endif
 
 // Independent accumulation chains of the row sum (see softmax_tile).
