@@ -28,8 +28,11 @@
  * No blocking, fusion, streaming softmax or reordering: a reader can check it
  * against the definition by eye.  Threads (OpenMP) split the query rows only.
  *
- * Layout: q, k, v are [B][H][N][d], d fastest, raw uint16 (fp16 or bf16 bit
- * patterns); o is [B][H][N][d] double; lse is [B][H][N] double.
+ * Layout: q, k, v are [B][H][N][d], d fastest, raw storage patterns: uint16
+ * for fp16 and bf16, uint8 for the 8-bit float (OCP E4M3, the "fp8" of the
+ * paper's second attention precision, Section 5.4); o is [B][H][N][d] double;
+ * lse is [B][H][N] double.  The element type only selects the decoder: the
+ * arithmetic above is the same for all three.
  */
 #include <math.h>
 #include <stddef.h>
@@ -42,6 +45,7 @@
 
 #define ATTN_REF_FP16 0
 #define ATTN_REF_BF16 1
+#define ATTN_REF_E4M3 2
 
 /* IEEE-754 binary16 -> double, exact.  1 sign, 5 exponent (bias 15), 10 fraction bits. */
 static double decode_fp16(uint16_t h)
@@ -75,15 +79,43 @@ static double decode_bf16(uint16_t h)
     return sign ? -mag : mag;
 }
 
-static double decode16(uint16_t h, int dtype)
+/*
+ * OCP 8-bit float E4M3 ("e4m3fn") -> double, exact.  1 sign, 4 exponent (bias 7), 3 fraction bits;
+ * no infinities: exponent 15 is an ordinary binade (up to 1.75 * 2^8 = 448) except that the
+ * all-ones pattern S.1111.111 is NaN.
+ */
+static double decode_e4m3(uint8_t b)
 {
+    int sign = (b >> 7) & 1;
+    int e = (b >> 3) & 0xf;
+    int f = b & 0x7;
+    double mag;
+    if (e == 0)
+        mag = ldexp((double)f, -9);                /* zero and subnormals: f * 2^-3 * 2^-6 */
+    else if (e == 15 && f == 7)
+        mag = NAN;
+    else
+        mag = ldexp(1.0 + (double)f / 8.0, e - 7);
+    return sign ? -mag : mag;
+}
+
+static int valid_dtype(int dtype)
+{
+    return dtype == ATTN_REF_FP16 || dtype == ATTN_REF_BF16 || dtype == ATTN_REF_E4M3;
+}
+
+/* Element `idx` of a tensor stored in the given element type. */
+static double decode_at(const void *base, long idx, int dtype)
+{
+    if (dtype == ATTN_REF_E4M3) return decode_e4m3(((const uint8_t *)base)[idx]);
+    uint16_t h = ((const uint16_t *)base)[idx];
     return dtype == ATTN_REF_BF16 ? decode_bf16(h) : decode_fp16(h);
 }
 
-/* Exported so that the decoders themselves can be pinned over all 65536 patterns. */
-void attn_ref_decode(const uint16_t *src, double *dst, long n, int dtype)
+/* Exported so that the decoders themselves can be pinned over all their patterns. */
+void attn_ref_decode(const void *src, double *dst, long n, int dtype)
 {
-    for (long i = 0; i < n; ++i) dst[i] = decode16(src[i], dtype);
+    for (long i = 0; i < n; ++i) dst[i] = decode_at(src, i, dtype);
 }
 
 static int resolve_threads(int nthreads)
@@ -145,13 +177,13 @@ static double attend_row(const double *qrow, const double *K, const double *V, d
  * If p_out is not NULL it receives the normalised probabilities
  * [B][H][N][N] (only sensible for small N; used by the row-sum pin).
  */
-int attn_ref_f64(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dtype,
+int attn_ref_f64(const void *q, const void *k, const void *v, int dtype,
                  double *o, double *lse, double *p_out,
                  int B, int H, int N, int d, double scale, int causal, int nthreads)
 {
     if (!q || !k || !v || !o || !lse) return -1;
     if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return -1;
-    if (dtype != ATTN_REF_FP16 && dtype != ATTN_REF_BF16) return -1;
+    if (!valid_dtype(dtype)) return -1;
     nthreads = resolve_threads(nthreads);
 
     const long n = N, dd = d;
@@ -165,11 +197,11 @@ int attn_ref_f64(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dt
     }
 
     for (long bh = 0; bh < (long)B * H; ++bh) {
-        const uint16_t *qh = q + bh * n * dd, *kh = k + bh * n * dd, *vh = v + bh * n * dd;
+        const long head = bh * n * dd;             /* first element of this head */
         for (long e = 0; e < n * dd; ++e) {
-            Q[e] = decode16(qh[e], dtype);
-            K[e] = decode16(kh[e], dtype);
-            V[e] = decode16(vh[e], dtype);
+            Q[e] = decode_at(q, head + e, dtype);
+            K[e] = decode_at(k, head + e, dtype);
+            V[e] = decode_at(v, head + e, dtype);
         }
         double *oh = o + bh * n * dd;
         double *lh = lse + bh * n;
@@ -190,16 +222,17 @@ int attn_ref_f64(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dt
 
 /*
  * The same definition for sampled query rows: rows[r] = {b, h, i} (3 ints per
- * sample); o_rows is [nrows][d], lse_rows is [nrows].  Used to check the
+ * sample); o_rows is [nrows][d], lse_rows is [nrows]; p_rows, when not NULL,
+ * receives the rows' normalised probabilities [nrows][N].  Used to check the
  * full-size workloads, where all B*H*N rows would take the CPU minutes.
  */
-int attn_ref_rows_f64(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dtype,
-                      const int *rows, int nrows, double *o_rows, double *lse_rows,
+int attn_ref_rows_f64(const void *q, const void *k, const void *v, int dtype,
+                      const int *rows, int nrows, double *o_rows, double *lse_rows, double *p_rows,
                       int B, int H, int N, int d, double scale, int causal, int nthreads)
 {
     if (!q || !k || !v || !rows || !o_rows || !lse_rows) return -1;
     if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || nrows < 0) return -1;
-    if (dtype != ATTN_REF_FP16 && dtype != ATTN_REF_BF16) return -1;
+    if (!valid_dtype(dtype)) return -1;
     for (int r = 0; r < nrows; ++r) {
         if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= H ||
             rows[3 * r + 2] < 0 || rows[3 * r + 2] >= N)
@@ -228,14 +261,15 @@ int attn_ref_rows_f64(const uint16_t *q, const uint16_t *k, const uint16_t *v, i
             for (int r = 0; r < nrows; ++r) {
                 long b = rows[3 * r], h = rows[3 * r + 1], i = rows[3 * r + 2];
                 long bh = b * H + h;
-                const uint16_t *kh = k + bh * n * dd, *vh = v + bh * n * dd;
-                const uint16_t *qr = q + (bh * n + i) * dd;
+                const long head = bh * n * dd;
                 for (long e = 0; e < n * dd; ++e) {
-                    K[e] = decode16(kh[e], dtype);
-                    V[e] = decode16(vh[e], dtype);
+                    K[e] = decode_at(k, head + e, dtype);
+                    V[e] = decode_at(v, head + e, dtype);
                 }
-                for (long t = 0; t < dd; ++t) Qr[t] = decode16(qr[t], dtype);
+                for (long t = 0; t < dd; ++t) Qr[t] = decode_at(q, head + i * dd + t, dtype);
                 lse_rows[r] = attend_row(Qr, K, V, srow, o_rows + (long)r * dd, i, n, dd, scale, causal);
+                if (p_rows)                        /* the row's normalised probabilities */
+                    for (long j = 0; j < n; ++j) p_rows[(long)r * n + j] = srow[j];
             }
         }
         free(K); free(V); free(Qr); free(srow);

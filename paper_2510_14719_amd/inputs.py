@@ -1,8 +1,9 @@
 """Seeded synthetic inputs for the attention-forward workloads.
 
 This module holds none of the method's arithmetic: it draws random numbers,
-rounds them to 16-bit storage and returns raw ``uint16`` bit patterns, so the
-CPU oracle and the GPU library are fed identical bits.  It is the only module
+rounds them to their storage type and returns raw bit patterns (``uint16`` for
+fp16 and bf16, ``uint8`` for the 8-bit float E4M3), so the CPU oracle and the
+GPU library are fed identical bits.  It is the only module
 both sides' tests import.
 
 The paper's attention sweep (Section 5.4: batch 4, head dimension 128, sequence
@@ -18,6 +19,7 @@ import numpy as np
 
 FP16 = 0
 BF16 = 1
+E4M3 = 2     # OCP 8-bit float: 1 sign, 4 exponent (bias 7), 3 fraction bits, largest finite 448, no infinities
 
 
 @dataclass(frozen=True)
@@ -27,7 +29,7 @@ class Workload:
     H: int
     N: int
     d: int
-    dtype: int          # FP16 or BF16
+    dtype: int          # FP16, BF16 or E4M3 (element type of Q, K, V)
     causal: bool
     peaky: bool = False  # 5 % of the K rows of every head multiplied by 8
     seed: int = 0
@@ -53,6 +55,15 @@ WORKLOADS = {
     "c5": Workload("c5", 2, 32, 8192, 128, BF16, True, peaky=True, seed=5000),
 }
 
+# The same shapes in the paper's second attention precision (Section 5.4, "FP8"): Q, K, V drawn as
+# above and rounded to E4M3.  c1/c3/c4/c5 with the element type changed and seeds of their own.
+FP8_WORKLOADS = {
+    "f1": Workload("f1", 1, 2, 128, 128, E4M3, False, seed=11000),
+    "f3": Workload("f3", 4, 16, 4096, 128, E4M3, False, seed=13000),
+    "f4": Workload("f4", 1, 16, 16384, 128, E4M3, False, seed=14000),
+    "f5": Workload("f5", 2, 32, 8192, 128, E4M3, True, peaky=True, seed=15000),
+}
+
 
 def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
     """float32 -> IEEE binary16 bit patterns, round to nearest even."""
@@ -66,12 +77,30 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
 
 
+def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """float32 -> E4M3 bit patterns (uint8), round to nearest even, saturating at +-448; NaN -> 0x7f."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    a = np.abs(x).astype(np.float64)
+    m, e = np.frexp(a)                               # a = m * 2^e, m in [0.5, 1)
+    t = np.rint(m * 16.0)                            # 4 significant bits, ties to even
+    e = np.where(t == 16.0, e + 1, e)
+    t = np.where(t == 16.0, 8.0, t)
+    normal = ((e + 6).astype(np.int64) << 3) | (t.astype(np.int64) - 8)
+    sub = np.rint(a * 512.0).astype(np.int64)        # below 2^-6: multiples of 2^-9 (8 = the smallest normal)
+    code = np.where(a < 2.0 ** -6, sub, normal)
+    code = np.where(a > 448.0, 0x7E, code)           # saturate (464 and above would round past the largest finite)
+    code = np.where(np.isnan(a), 0x7F, np.minimum(code, 0x7E))
+    return (code | (np.signbit(x).astype(np.int64) << 7)).astype(np.uint8)
+
+
 def to_bits(x: np.ndarray, dtype: int) -> np.ndarray:
+    if dtype == E4M3:
+        return f32_to_e4m3_bits(x)
     return f32_to_bf16_bits(x) if dtype == BF16 else f32_to_f16_bits(x)
 
 
 def normal_bits(shape, dtype: int, seed: int, std: float = 1.0) -> np.ndarray:
-    """i.i.d. N(0, std^2) drawn in float32 from Philox(seed), rounded to 16 bit."""
+    """i.i.d. N(0, std^2) drawn in float32 from Philox(seed), rounded to the storage type."""
     rng = np.random.Generator(np.random.Philox(seed))
     x = rng.standard_normal(size=shape, dtype=np.float32)
     if std != 1.0:
@@ -81,7 +110,7 @@ def normal_bits(shape, dtype: int, seed: int, std: float = 1.0) -> np.ndarray:
 
 def make_qkv(B: int, H: int, N: int, d: int, dtype: int, seed: int, peaky: bool = False,
              peak_frac: float = 0.05, peak_gain: float = 8.0):
-    """Q, K, V as ``[B,H,N,d]`` uint16 bit patterns; seeds ``seed, seed+1, seed+2``.
+    """Q, K, V as ``[B,H,N,d]`` bit patterns (uint16, or uint8 for E4M3); seeds ``seed, seed+1, seed+2``.
 
     With ``peaky`` a fixed seeded choice of ``floor(peak_frac*N)`` distinct key
     rows of every (b, h) is multiplied by ``peak_gain`` in float32 before the
