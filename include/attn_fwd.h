@@ -69,7 +69,35 @@ int attn_fwd_bf16(const void *q, const void *k, const void *v, void *o, float *l
 int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
              int B, int H, int N, int d, float scale, int causal, void *stream, int dtype);
 
-/* Host-only argument check: what the entry points above would return before launching. */
+/*
+ * The same operation on 8-bit-float inputs, the second precision ("FP8") in which the paper
+ * evaluates attention (Section 5.4).  The paper fixes neither the format nor the scaling convention;
+ * the reading taken here:
+ *   q, k, v  DEVICE pointers, read only, [B][H][N][d] contiguous, ONE byte per element in OCP E4M3
+ *            (1 sign, 4 exponent bits with bias 7, 3 fraction bits, largest finite 448, no
+ *            infinities, S.1111.111 = NaN): the 8-bit float the gfx950 matrix cores take.  There are
+ *            no separate scale tensors: a per-tensor dequantisation factor of Q and of K is folded
+ *            into `scale` by the caller, one of V multiplies O afterwards.
+ *   o        DEVICE pointer, written, [B][H][N][d] in the 16-bit type out_dtype (ATTN_FWD_FP16 or
+ *            ATTN_FWD_BF16); must not overlap q, k or v.
+ *   lse      DEVICE pointer, written, [B][H][N] float32.
+ * Both contractions run on the 8-bit matrix-core path: the probabilities are rounded to E4M3 (round
+ * to nearest even) before P V, accumulation is fp32, and O is normalised by the sum of the ROUNDED
+ * probabilities, so every output row is a convex combination of V rows; LSE is the natural log of
+ * that same sum (plus the reference maximum).  All other arguments, the alignment rule, ownership,
+ * asynchrony and the return codes are those of attn_fwd.
+ */
+int attn_fwd_fp8(const void *q, const void *k, const void *v, void *o, float *lse,
+                 int B, int H, int N, int d, float scale, int causal, void *stream, int out_dtype);
+
+/* Host-only argument check of attn_fwd_fp8. */
+int attn_fwd_fp8_check_args(const void *q, const void *k, const void *v, const void *o, const float *lse,
+                            int B, int H, int N, int d, float scale, int out_dtype);
+
+/* Launch parameters of the 8-bit-float kernel for head dimension d; `which` as in attn_fwd_tile_param. */
+int attn_fwd_fp8_tile_param(int d, int which);
+
+/* Host-only argument check: what the 16-bit entry points above would return before launching. */
 int attn_fwd_check_args(const void *q, const void *k, const void *v, const void *o, const float *lse,
                         int B, int H, int N, int d, float scale, int dtype);
 

@@ -5,7 +5,7 @@ imported lazily so that the input generators can be used on a machine that has
 no built library.
 """
 
-__all__ = ["attn_fwd", "attn_fwd_f16", "attn_fwd_bf16", "AttnFwdError", "load_library"]
+__all__ = ["attn_fwd", "attn_fwd_f16", "attn_fwd_bf16", "attn_fwd_fp8", "AttnFwdError", "load_library"]
 
 
 def __getattr__(name):

@@ -49,6 +49,12 @@ def load_library() -> ctypes.CDLL:
         lib.attn_fwd.argtypes = common + [ci]
         lib.attn_fwd_check_args.restype = ci
         lib.attn_fwd_check_args.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, cf, ci]
+        lib.attn_fwd_fp8.restype = ci
+        lib.attn_fwd_fp8.argtypes = common + [ci]
+        lib.attn_fwd_fp8_check_args.restype = ci
+        lib.attn_fwd_fp8_check_args.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, cf, ci]
+        lib.attn_fwd_fp8_tile_param.restype = ci
+        lib.attn_fwd_fp8_tile_param.argtypes = [ci, ci]
         lib.attn_fwd_strerror.restype = ctypes.c_char_p
         lib.attn_fwd_strerror.argtypes = [ci]
         lib.attn_fwd_version.restype = ci
@@ -141,6 +147,36 @@ def attn_fwd_bf16(q, k, v, o, lse, B, H, N, d, scale, causal, stream=None) -> No
                                           float(scale), int(bool(causal)), _stream_handle(stream)))
     if rc != 0:
         raise AttnFwdError(rc, strerror(rc))
+
+
+def attn_fwd_fp8_raw(q, k, v, o, lse, B, H, N, d, scale, causal, stream, out_dtype) -> int:
+    """The C call itself; returns its code without raising."""
+    return int(load_library().attn_fwd_fp8(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), int(B), int(H), int(N), int(d),
+                                           float(scale), int(bool(causal)), _stream_handle(stream), int(out_dtype)))
+
+
+def attn_fwd_fp8(q, k, v, o, lse, B, H, N, d, scale, causal, stream=None, out_dtype=None) -> None:
+    """``attn_fwd_fp8`` of the C ABI: Q, K, V one byte per element (E4M3), O in fp16 or bf16.
+
+    ``out_dtype`` defaults to the element type of ``o``.  Asynchronous, like ``attn_fwd``.
+    """
+    if out_dtype is None:
+        import torch
+        if o.dtype == torch.float16:
+            out_dtype = FP16
+        elif o.dtype == torch.bfloat16:
+            out_dtype = BF16
+        else:
+            raise ValueError("pass out_dtype=FP16/BF16 for an output tensor of type %s" % o.dtype)
+    rc = attn_fwd_fp8_raw(q, k, v, o, lse, B, H, N, d, scale, causal, stream, out_dtype)
+    if rc != 0:
+        raise AttnFwdError(rc, strerror(rc))
+
+
+def fp8_tile_params(d: int) -> dict:
+    lib = load_library()
+    return {"BM": lib.attn_fwd_fp8_tile_param(d, 0), "BN": lib.attn_fwd_fp8_tile_param(d, 1),
+            "stages": lib.attn_fwd_fp8_tile_param(d, 2), "threads": lib.attn_fwd_fp8_tile_param(d, 3)}
 
 
 def tile_params(d: int, causal: bool = False) -> dict:

@@ -64,6 +64,40 @@ int attn_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* l
     return attn_fwd(q, k, v, o, lse, B, H, N, d, scale, causal, stream, ATTN_FWD_BF16);
 }
 
+int attn_fwd_fp8_check_args(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                            int B, int H, int N, int d, float scale, int out_dtype)
+{
+    if (!q || !k || !v || !o || !lse) return ATTN_FWD_ERR_NULL;
+    if (B < 1 || H < 1 || N < 1 || (d != 64 && d != 128)) return ATTN_FWD_ERR_SHAPE;
+    if (out_dtype != ATTN_FWD_FP16 && out_dtype != ATTN_FWD_BF16) return ATTN_FWD_ERR_SHAPE;
+    if (!std::isfinite(scale) || !(scale > 0.0f)) return ATTN_FWD_ERR_SCALE;
+    const std::uintptr_t mis = reinterpret_cast<std::uintptr_t>(q) | reinterpret_cast<std::uintptr_t>(k) |
+                               reinterpret_cast<std::uintptr_t>(v) | reinterpret_cast<std::uintptr_t>(o) |
+                               reinterpret_cast<std::uintptr_t>(lse);
+    if (mis & 15u) return ATTN_FWD_ERR_ALIGN;
+    // The kernel indexes inside one head with 32-bit byte offsets and numbers its workgroups with an int.
+    const unsigned long long head_elems = (unsigned long long)N * (unsigned long long)d;
+    if (2ull * head_elems >= (1ull << 31)) return ATTN_FWD_ERR_OVERFLOW;
+    const int bm = attn_fp8_launch_tile_param(d, 0);
+    const unsigned long long tiles = ((unsigned long long)N + bm - 1) / bm * (unsigned long long)B * (unsigned long long)H;
+    if (tiles >= (1ull << 31)) return ATTN_FWD_ERR_OVERFLOW;
+    const unsigned long long in_bytes = head_elems * (unsigned long long)B * (unsigned long long)H, out_bytes = 2ull * in_bytes;
+    if (overlaps(o, out_bytes, q, in_bytes) || overlaps(o, out_bytes, k, in_bytes) || overlaps(o, out_bytes, v, in_bytes))
+        return ATTN_FWD_ERR_ALIAS;
+    return ATTN_FWD_OK;
+}
+
+int attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* lse,
+                 int B, int H, int N, int d, float scale, int causal, void* stream, int out_dtype)
+{
+    const int rc = attn_fwd_fp8_check_args(q, k, v, o, lse, B, H, N, d, scale, out_dtype);
+    if (rc != ATTN_FWD_OK) return rc;
+    AttnLaunchArgs a{q, k, v, o, lse, B, H, N, d, scale, causal != 0, out_dtype, stream};
+    return attn_fp8_launch(a) == 0 ? ATTN_FWD_OK : ATTN_FWD_ERR_LAUNCH;
+}
+
+int attn_fwd_fp8_tile_param(int d, int which) { return attn_fp8_launch_tile_param(d, which); }
+
 const char* attn_fwd_strerror(int code)
 {
     switch (code) {

@@ -18,6 +18,14 @@
 #define ATTN_CFG_STAGES 4    // LDS ring depth
 #endif
 
+// Keys per K/V tile of the 8-bit-float kernel, by head dimension.
+#ifndef ATTN8_CFG_BN_D128
+#define ATTN8_CFG_BN_D128 64
+#endif
+#ifndef ATTN8_CFG_BN_D64
+#define ATTN8_CFG_BN_D64 128
+#endif
+
 struct AttnLaunchArgs {
     const void* q;
     const void* k;
@@ -27,7 +35,7 @@ struct AttnLaunchArgs {
     int B, H, N, d;
     float scale;
     int causal;
-    int dtype;      // 0 = fp16, 1 = bf16
+    int dtype;      // 0 = fp16, 1 = bf16 (16-bit kernels: of Q, K, V and O; 8-bit-float kernel: of O)
     void* stream;   // hipStream_t
 };
 
@@ -36,6 +44,11 @@ int attn_launch(const AttnLaunchArgs& a);
 
 // Query rows per workgroup (0), keys per tile (1), LDS stages (2), threads per workgroup (3).
 int attn_launch_tile_param(int d, int causal, int which);
+
+// The same for the kernel that takes Q, K, V in E4M3 (attn_fwd_fp8_kernel.hip); a.dtype is the type of O.
+int attn_fp8_launch(const AttnLaunchArgs& a);
+// Query rows per workgroup (0), keys per tile (1), LDS stages (2), threads per workgroup (3).
+int attn_fp8_launch_tile_param(int d, int which);
 
 // Register-only MFMA stream (mfma_probe.hip): `workgroups` workgroups of mfma_probe_threads() threads,
 // every wave issuing iters * 8 MFMAs of the given element type; one float per thread is written to sink.

@@ -52,3 +52,67 @@ def check(o_gpu, lse_gpu, o_ref, lse_ref, what="", tol_o_max=TOL_O_MAX, tol_o_me
     assert eo.max() <= tol_o_max, msg
     assert eo.mean() <= tol_o_mean, msg
     assert el.max() <= tol_lse, msg
+
+
+# ---------------------------------------------------------------- 8-bit-float (E4M3) inputs
+def run_gpu_fp8(q, k, v, out_dtype, scale, causal):
+    """Launch ``attn_fwd_fp8`` on [B,H,N,d] uint8 numpy inputs (E4M3 patterns).  Returns (O f64, LSE f64);
+    the outputs sit inside larger buffers whose margins are checked for stray writes."""
+    B, H, N, d = q.shape
+    dq, dk, dv = (torch.from_numpy(x).cuda() for x in (q, k, v))
+    n_o, n_l = B * H * N * d, B * H * N
+    pad = 256
+    obuf = torch.full((n_o + 2 * pad,), 0x7B7B, dtype=torch.int16, device="cuda")
+    lbuf = torch.full((n_l + 2 * pad,), -777.0, dtype=torch.float32, device="cuda")
+    o = obuf[pad:pad + n_o]
+    lse = lbuf[pad:pad + n_l]
+    binding.attn_fwd_fp8(dq, dk, dv, o, lse, B, H, N, d, scale, causal, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    assert bool((obuf[:pad] == 0x7B7B).all()) and bool((obuf[pad + n_o:] == 0x7B7B).all()), "O guard words overwritten"
+    assert bool((lbuf[:pad] == -777.0).all()) and bool((lbuf[pad + n_l:] == -777.0).all()), "LSE guard words overwritten"
+    return bits_to_f64(o.reshape(B, H, N, d), out_dtype), lse.reshape(B, H, N).to(torch.float64).cpu().numpy()
+
+
+def e4m3_to_f64(bits: np.ndarray) -> np.ndarray:
+    """E4M3 patterns -> float64 (decoded by torch, not by the oracle)."""
+    return torch.from_numpy(np.ascontiguousarray(bits)).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+
+
+def fp8_bounds(p, vf, o_ref, out_dtype):
+    """Worst-case error of the 8-bit path against the exact result, per output element.
+
+    The kernel rounds every unnormalised probability to E4M3 (round to nearest even) before P V
+    and normalises by the sum of the rounded values.  With p_j the exact normalised probabilities
+    of a row, the weight the kernel gives key j differs from p_j by at most
+        E_j = min(p_j, max(2^-4 p_j, 2^-10 max_j p_j))
+    (half a unit in the last of 3 fraction bits for normal values; below 2^-6 of the reference,
+    which is never smaller than the row maximum, the spacing is 2^-9; a weight that rounds to
+    zero is off by itself), so
+        |O_gpu - O| <= (sum_j E_j |v_j| + |O| sum_j E_j) / (1 - sum_j E_j)  + rounding of the output
+        |LSE_gpu - LSE| <= -ln(1 - sum_j E_j)
+    ``p``: [..., n, N] probability rows, ``vf``: [..., N, d] values, ``o_ref``: [..., n, d].
+    Returns (bound_O [..., n, d], bound_LSE [..., n]).
+    """
+    E = np.minimum(p, np.maximum(p * 2.0 ** -4, p.max(axis=-1, keepdims=True) * 2.0 ** -10))
+    se = E.sum(axis=-1)
+    assert se.max() < 0.5
+    u_out = 2.0 ** -8 if out_dtype == I.BF16 else 2.0 ** -11
+    bo = ((E @ np.abs(vf)) + np.abs(o_ref) * se[..., None]) / (1.0 - se[..., None])
+    bo = bo * 1.01 + np.abs(o_ref) * u_out * 1.01 + 1e-4      # fp32 accumulation, hardware exp2, output rounding
+    bl = -np.log1p(-se) * 1.01 + 1e-4
+    return bo, bl
+
+
+def check_fp8(o_gpu, lse_gpu, o_ref, lse_ref, bound_o, bound_l, what=""):
+    """Every element inside its worst-case bound; the mean error far inside (rounding errors are
+    zero-mean and largely cancel over the keys of a row)."""
+    assert np.isfinite(o_gpu).all(), what + ": non-finite O"
+    assert np.isfinite(lse_gpu).all(), what + ": non-finite LSE"
+    eo, el = np.abs(o_gpu - o_ref), np.abs(lse_gpu - lse_ref)
+    msg = "%s: O max %.3e mean %.3e (bound mean %.3e, worst ratio %.2f), LSE max %.3e mean %.3e (worst ratio %.2f)" % (
+        what, eo.max(), eo.mean(), bound_o.mean(), (eo / bound_o).max(), el.max(), el.mean(), (el / bound_l).max())
+    print(msg, flush=True)
+    assert (eo <= bound_o).all(), msg
+    assert (el <= bound_l).all(), msg
+    assert eo.mean() <= 0.35 * bound_o.mean() + 1e-4, msg
+    assert el.mean() <= 0.35 * bound_l.mean() + 1e-4, msg

@@ -68,6 +68,31 @@ def test_argument_validation_needs_no_gpu(lib):
     assert f(q, k, v, k + 16, l, 2, 4, 1024, 128, 0.088, 0) == -7
 
 
+def test_fp8_argument_validation_needs_no_gpu(lib):
+    q, k, v, o, l = 0x10000000, 0x20000000, 0x30000000, 0x40000000, 0x50000000
+    f = lib.attn_fwd_fp8_check_args
+    assert f(q, k, v, o, l, 2, 4, 1024, 128, 0.088, 0) == 0
+    assert f(q, k, v, o, l, 2, 4, 1024, 64, 0.088, 1) == 0
+    assert f(q, 0, v, o, l, 2, 4, 1024, 128, 0.088, 0) == -1
+    assert f(q, k, v, o, l, 2, 0, 1024, 128, 0.088, 0) == -2
+    assert f(q, k, v, o, l, 2, 4, 1024, 256, 0.088, 0) == -2
+    assert f(q, k, v, o, l, 2, 4, 1024, 128, 0.088, 2) == -2       # O is fp16 or bf16
+    assert f(q, k, v, o, l, 2, 4, 1024, 128, -0.5, 0) == -3
+    assert f(q, k + 4, v, o, l, 2, 4, 1024, 128, 0.088, 0) == -4
+    assert f(q, k, v, o, l, 1, 1, 2 ** 23, 128, 0.088, 0) == -5
+    # O has two bytes per element, the inputs one: 2*4*1024*128 = 1 MiB of input, 2 MiB of output
+    assert f(q, k, v, q, l, 2, 4, 1024, 128, 0.088, 0) == -7
+    assert f(q, k, v, q - (2 << 20) + 16, l, 2, 4, 1024, 128, 0.088, 0) == -7
+    assert f(q, k, v, q - (2 << 20), l, 2, 4, 1024, 128, 0.088, 0) == 0
+    assert f(q, k, v, q + (1 << 20), l, 2, 4, 1024, 128, 0.088, 0) == 0
+    assert lib.attn_fwd_fp8(None, None, None, None, None, 1, 1, 64, 128, 0.125, 0, None, 0) == -1
+    for d in (64, 128):
+        bm, bn, st, th = (lib.attn_fwd_fp8_tile_param(d, w) for w in range(4))
+        assert bm == 256 and bn % 64 == 0 and th == 512
+        assert st * 2 * bn * d <= 160 * 1024
+    assert lib.attn_fwd_fp8_tile_param(96, 0) == -1
+
+
 def test_entry_points_return_argument_errors_without_launching(lib):
     # the full entry points run the same validation first; with a NULL pointer no HIP call is made
     assert lib.attn_fwd_f16(None, None, None, None, None, 1, 1, 64, 64, 0.125, 0, None) == -1
