@@ -26,7 +26,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {0: 2500.0, 1: 2500.0}   # MI355X dense MFMA peak, fp16 and bf16
+PEAK_TFLOPS = {0: 2500.0, 1: 2500.0, 2: 5000.0}   # MI355X dense MFMA peak: fp16, bf16, fp8
+DTYPE_NAME = {0: "fp16", 1: "bf16", 2: "fp8-e4m3"}
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each scaled by
 # what the counter reads for a 1 GiB copy); a profile's figure, not measured by this script.
@@ -35,7 +36,7 @@ MEASURED_TRAFFIC = {"c4": ((163994.6 * 2.000 + 67133.9 * 1.000) * 1024.0, "profi
 
 def describe(w) -> str:
     return "%s: B=%d H=%d N=%d d=%d %s %s%s" % (
-        w.name, w.B, w.H, w.N, w.d, "fp16" if w.dtype == 0 else "bf16",
+        w.name, w.B, w.H, w.N, w.d, DTYPE_NAME[w.dtype],
         "causal" if w.causal else "non-causal", " peaky-K" if w.peaky else "")
 
 
@@ -168,7 +169,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=25)
-    ap.add_argument("--workload", default="c4")
+    ap.add_argument("--workload", default="c4",
+                    help="c1 ... c5: the 16-bit configurations (c4 = headline, the default); "
+                         "f1, f3, f4, f5: the same shapes with Q, K, V in 8-bit float (E4M3), O in fp16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the register-only MFMA stream that measures the sustained matrix-core rate")
@@ -192,16 +195,25 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 3
     binding.load_library()
-    w = I.WORKLOADS[args.workload]
+    fp8 = args.workload in I.FP8_WORKLOADS
+    w = I.FP8_WORKLOADS[args.workload] if fp8 else I.WORKLOADS[args.workload]
+    out_dtype = I.FP16 if fp8 else w.dtype      # element type of O
 
     # ---- inputs: seeded synthetic tensors, resident in HBM before anything is timed
-    q, k, v = (torch.from_numpy(x.view("int16")).cuda() for x in I.make_workload(w))
-    o = torch.empty_like(q)
+    if fp8:
+        q, k, v = (torch.from_numpy(x).cuda() for x in I.make_workload(w))
+        o = torch.empty((w.B, w.H, w.N, w.d), dtype=torch.int16, device="cuda")
+    else:
+        q, k, v = (torch.from_numpy(x.view("int16")).cuda() for x in I.make_workload(w))
+        o = torch.empty_like(q)
     lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
     def step():
-        binding.attn_fwd(q, k, v, o, lse, w.B, w.H, w.N, w.d, w.scale, w.causal, stream=stream, dtype=w.dtype)
+        if fp8:
+            binding.attn_fwd_fp8(q, k, v, o, lse, w.B, w.H, w.N, w.d, w.scale, w.causal, stream=stream, out_dtype=out_dtype)
+        else:
+            binding.attn_fwd(q, k, v, o, lse, w.B, w.H, w.N, w.d, w.scale, w.causal, stream=stream, dtype=w.dtype)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB read + 1 GiB written
@@ -239,10 +251,10 @@ def main() -> int:
         import numpy as np
         from oracle import attn_ref
         rows = I.sample_rows(w.B, w.H, w.N, 16, seed=w.seed + 11, always=[(0, 0, 0), (w.B - 1, w.H - 1, w.N - 1)])
-        qn, kn, vn = (x.cpu().numpy().view("uint16") for x in (q, k, v))
+        qn, kn, vn = (x.cpu().numpy().view("uint8" if fp8 else "uint16") for x in (q, k, v))
         o_ref, l_ref = attn_ref.attn_ref_rows(qn, kn, vn, w.dtype, rows, w.scale, w.causal)
         idx = np.asarray(rows)
-        of = o.view(torch.float16 if w.dtype == 0 else torch.bfloat16)[idx[:, 0], idx[:, 1], idx[:, 2]].double().cpu().numpy()
+        of = o.view(torch.float16 if out_dtype == 0 else torch.bfloat16)[idx[:, 0], idx[:, 1], idx[:, 2]].double().cpu().numpy()
         lf = lse[idx[:, 0], idx[:, 1], idx[:, 2]].double().cpu().numpy()
         parity = {"rows": len(rows), "o_max_abs": float(np.abs(of - o_ref).max()), "o_mean_abs": float(np.abs(of - o_ref).mean()),
                   "lse_max_abs": float(np.abs(lf - l_ref).max())}
@@ -258,9 +270,10 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16" if w.dtype == 0 else "bf16",
+        "dtype": {0: "f16", 1: "bf16", 2: "f8e4m3"}[w.dtype],
         "data": "synthetic",
-        "config": {"workload": describe(w), "scale": w.scale, "tile": binding.tile_params(w.d, w.causal),
+        "config": {"workload": describe(w), "scale": w.scale,
+                   "tile": binding.fp8_tile_params(w.d) if fp8 else binding.tile_params(w.d, w.causal),
                    "flops_per_step": w.flops, "wall_s_timed_region": wall},
         "frac_of_mfma_peak": tflops / peak,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
@@ -271,7 +284,10 @@ def main() -> int:
         "context": {"paper_h100_fp16_mha_tflops": 654.0,
                     "paper_workload": "H100 SXM5, L=16384, batch 4, d=128 (Section 5.6); other hardware, not a target"},
     }
-    if not args.no_mfma_probe:
+    if fp8:
+        out["context"] = {"paper": "the paper plots FP8 attention (Section 5.4) without printing a number for it",
+                          "p_precision": "probabilities rounded to E4M3 before P V; O in fp16"}
+    if not args.no_mfma_probe and not fp8:
         # outside the timed region: the measured MFMA-only rates next to the datasheet peak
         sus = mfma_sustained(binding, torch, w.dtype, stream)
         sus["unit"] = "TFLOP/s"

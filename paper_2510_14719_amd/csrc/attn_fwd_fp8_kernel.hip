@@ -53,9 +53,28 @@ constexpr float RESCALE_LOG2_FP8 = 8.0f;
 #define ATTN8_FWIN 2
 #endif
 
+// Where the row sum of the probabilities is computed: 0 = on the matrix cores (a block of ones next to
+// V^T: the sum of the ROUNDED probabilities, no vector-ALU work), 1 = on the vector ALU (fp32 additions
+// of the unrounded probabilities, one per score, and one MFMA less per 64 keys).
+#ifndef ATTN8_ROWSUM_VALU
+#define ATTN8_ROWSUM_VALU 0
+#endif
+
 // Block scales of the MFMA: 0 selects the plain (unscaled) instruction.
 #ifndef ATTN8_SCALE_WORD
 #define ATTN8_SCALE_WORD 0
+#endif
+
+#ifdef ATTN8_TIMING
+// Profiling builds only: per-wave cycle totals of the main-loop sections of the first workgroups.
+constexpr int DBG8_WGS = 1024, DBG8_SLOTS = 8;
+__device__ unsigned long long attn8_dbg[DBG8_WGS * 8 * DBG8_SLOTS];
+#define TSTAMP8(var) unsigned long long var; __builtin_amdgcn_sched_barrier(0); \
+    asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(var) :: "memory"); __builtin_amdgcn_sched_barrier(0)
+#define TACC8(slot, a, b) dbg_acc[slot] += (b) - (a)
+#else
+#define TSTAMP8(var)
+#define TACC8(slot, a, b)
 #endif
 
 __device__ __forceinline__ f32x16 mfma_fp8(i32x8 a, i32x8 b, f32x16 c) {
@@ -183,7 +202,7 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
 
     f32x16 O[DB], L, S[KB];                     // L: the ones block of the second contraction = row sums
     int pw[KB * 4];                             // P of the current tile, four E4M3 values per word
-    float m_run;
+    float m_run, l_valu = 0.f;                  // l_valu: this lane's share of the row sum when the vector ALU keeps it
 
     // per-lane LDS read offsets (the rest of every address is an immediate)
     const int k_lane = g * 2 * KCOL + lr * 16;
@@ -214,7 +233,8 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     // ---- MFMA burst on one stage: U (O^T += V^T P^T and the ones block, with the P in pw) and/or
     // T (S^T = K Q^T), as one stream of MFMAs whose LDS fragments are requested FWIN MFMAs ahead.
     auto mfma_burst = [&](auto do_u, auto do_t, const char* stage_ptr) __attribute__((always_inline)) {
-        constexpr int NU = decltype(do_u)::value ? KC * (DB + 1) : 0;   // per chunk: DB feature blocks, then the ones block
+        constexpr int UB = ATTN8_ROWSUM_VALU ? DB : DB + 1;             // per chunk: DB feature blocks, then the ones block
+        constexpr int NU = decltype(do_u)::value ? KC * UB : 0;
         constexpr int NT = decltype(do_t)::value ? KB * FK : 0;
         constexpr int NF = NU + NT;
         constexpr int FWIN = ATTN8_FWIN < NF ? ATTN8_FWIN : NF;
@@ -223,7 +243,7 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         i32x8 fr[NF];
         auto fetch = [&](int f) __attribute__((always_inline)) {
             if (f < NU) {
-                const int kc = f / (DB + 1), db = f % (DB + 1);
+                const int kc = f / UB, db = f % UB;
                 if (db < DB) fr[f] = read_vf(sv, kc, db);
                 else fr[f] = i32x8(0x38383838);                         // 1.0 in every byte
             } else {
@@ -232,7 +252,7 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         };
         auto run_mfma = [&](int f) __attribute__((always_inline)) {
             if (f < NU) {
-                const int kc = f / (DB + 1), db = f % (DB + 1);
+                const int kc = f / UB, db = f % UB;
                 i32x8 p;
 #pragma unroll
                 for (int t = 0; t < 8; ++t) p[t] = pw[kc * 8 + t];
@@ -280,6 +300,7 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         const float alpha = __builtin_amdgcn_exp2f((m_old - m_use) * scale_log2e);
         const float neg_mc = -m_use * scale_log2e;
         m_run = m_use;
+        float sum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -291,7 +312,9 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
                 int w = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, 0, false);
                 w = __builtin_amdgcn_cvt_pk_fp8_f32(p2, p3, w, true);
                 pw[kb * 4 + t] = w;
+                if (ATTN8_ROWSUM_VALU) { sum[0] += p0; sum[1] += p1; sum[2] += p2; sum[3] += p3; }
             }
+        if (ATTN8_ROWSUM_VALU) l_valu = l_valu * alpha + ((sum[0] + sum[1]) + (sum[2] + sum[3]));
         if (__builtin_amdgcn_ballot_w64(upd) != 0) {
 #pragma unroll
             for (int db = 0; db < DB; ++db) O[db] = O[db] * alpha;
@@ -311,7 +334,12 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     auto epilogue = [&]() __attribute__((always_inline)) {
         uint16_t* oh = o + head_off;
         float* lh = lse + (size_t)bh * N;
-        const float l_tot = L[0];               // every element of the ones block holds the row sum
+        float l_tot = L[0];                     // every element of the ones block holds the row sum
+        if (ATTN8_ROWSUM_VALU) {                // the two lanes of a query hold half of the keys each
+            float a = l_valu, b = l_valu;
+            asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+            l_tot = a + b;
+        }
         const float inv = 1.0f / l_tot;
         const int row = wq0 + lr;
         if (row < N) {
@@ -343,6 +371,10 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
 #pragma unroll
     for (int db = 0; db < DB; ++db) O[db] = f32x16(0.f);
     __builtin_amdgcn_s_barrier();               // stages -1, 0, 1 are complete for every wave
+#ifdef ATTN8_TIMING
+    unsigned long long dbg_acc[DBG8_SLOTS] = {};
+    const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime(), ct0 = __builtin_readcyclecounter();
+#endif
 
     if (!group_b) {
         // group A, iteration j: [U_{j-1}, T_j] then C_j; both contractions read stage j-1
@@ -353,10 +385,16 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         int j = 1;
         if (j < nt_w) {
             do {                                // bottom-tested: the accumulators are updated in place
+                TSTAMP8(t0);
                 wait_stage(j);
+                TSTAMP8(t1);
                 mfma_burst(std::true_type{}, std::true_type{}, stage_ptr(j - 1));
+                TSTAMP8(t2);
                 if (j + 2 < nt) issue_stage(j + 2);
+                TSTAMP8(t3);
                 softmax_tile(j);
+                TSTAMP8(t4);
+                TACC8(0, t0, t1); TACC8(1, t1, t2); TACC8(2, t2, t3); TACC8(3, t3, t4);
             } while (++j < nt_w);
         }
         if (j < nt) wait_stage(j);                                                       // j == nt_w
@@ -373,10 +411,16 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         int j = 0;
         if (j + 1 < nt_w) {
             do {
+                TSTAMP8(t0);
                 wait_stage(j);
+                TSTAMP8(t1);
                 if (j + 2 < nt) issue_stage(j + 2);
+                TSTAMP8(t2);
                 softmax_tile(j);
+                TSTAMP8(t3);
                 mfma_burst(std::true_type{}, std::true_type{}, stage_ptr(j));
+                TSTAMP8(t4);
+                TACC8(0, t0, t1); TACC8(2, t1, t2); TACC8(3, t2, t3); TACC8(1, t3, t4);
             } while (++j + 1 < nt_w);
         }
         wait_stage(j);                                                                   // j == nt_w - 1
@@ -389,7 +433,24 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         }
         epilogue();
     }
+#ifdef ATTN8_TIMING
+    if (blockIdx.x < DBG8_WGS && lane == 0) {
+        dbg_acc[5] = nt;
+        dbg_acc[6] = __builtin_amdgcn_s_memrealtime() - rt0;   // 100 MHz ticks
+        dbg_acc[7] = __builtin_readcyclecounter() - ct0;
+        for (int i = 0; i < DBG8_SLOTS; ++i) attn8_dbg[(blockIdx.x * 8 + wave) * DBG8_SLOTS + i] = dbg_acc[i];
+    }
+#endif
 }
+
+#ifdef ATTN8_TIMING
+}  // namespace
+extern "C" int attn8_dbg_read(unsigned long long* host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(attn8_dbg), sizeof(unsigned long long) * n);
+}
+namespace {
+#endif
 
 template <int OUT, int D, int BN, bool CAUSAL>
 int launch_fp8(const AttnLaunchArgs& a)

@@ -20,7 +20,7 @@
 
 // Keys per K/V tile of the 8-bit-float kernel, by head dimension.
 #ifndef ATTN8_CFG_BN_D128
-#define ATTN8_CFG_BN_D128 64
+#define ATTN8_CFG_BN_D128 128
 #endif
 #ifndef ATTN8_CFG_BN_D64
 #define ATTN8_CFG_BN_D64 128

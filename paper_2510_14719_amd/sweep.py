@@ -16,6 +16,9 @@ What the axes stand for on gfx950:
              ATTN_COPY_GROUP    which waves produce (issue the global -> LDS copies): 0 all, 2 group A, 1 group B
              ATTN_SUMCHAINS     independent row-sum chains of the softmax
              ATTN_PERSISTENT    persistent launch with the static tile schedule (causal d = 128)
+  attn_fp8   ATTN8_FWIN         the same for the 8-bit-float kernel
+             ATTN8_CFG_BN_D128  keys per K/V tile (one wait + barrier per tile; the LDS ring is 4 x 2 x BN x d bytes)
+             ATTN8_ROWSUM_VALU  row sums on the matrix cores (0: a block of ones next to V^T) or on the vector ALU (1)
   gemm       GEMM_STAGES        depth of the LDS ring (the paper's D): 4 or 5
              GEMM_COMPUTE_WAVES waves per workgroup: 8 x (128 x 64) or 4 x (128 x 128)
              GEMM_TAIL_READS    LDS requests allowed in flight across the tile boundary
@@ -35,9 +38,10 @@ VARIANT_DIR = os.path.join(HERE, "sweep_variants")
 GRIDS = {
     "attn": {"ATTN_FWIN": [1, 2, 4, 8], "ATTN_COPY_GROUP": [0, 2, 1], "ATTN_SUMCHAINS": [2, 4]},
     "attn_causal": {"ATTN_PERSISTENT": [0, 1], "ATTN_FWIN": [2, 4]},
+    "attn_fp8": {"ATTN8_FWIN": [1, 2, 3], "ATTN8_CFG_BN_D128": [128, 64], "ATTN8_ROWSUM_VALU": [0, 1]},
     "gemm": {"GEMM_STAGES": [4, 5], "GEMM_COMPUTE_WAVES": [8, 4], "GEMM_TAIL_READS": [0, 3]},
 }
-DEFAULTS = {"ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
+DEFAULTS = {"ATTN8_FWIN": 2, "ATTN8_CFG_BN_D128": 128, "ATTN8_ROWSUM_VALU": 0, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
             "GEMM_STAGES": 4, "GEMM_COMPUTE_WAVES": 8, "GEMM_TAIL_READS": 3}
 
 
@@ -77,6 +81,8 @@ def _load(path):
     vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
     lib.attn_fwd.restype = ci
     lib.attn_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, cf, ci, vp, ci]
+    lib.attn_fwd_fp8.restype = ci
+    lib.attn_fwd_fp8.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, cf, ci, vp, ci]
     lib.gemm_nt.restype = ci
     lib.gemm_nt.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci]
     return lib
@@ -103,6 +109,16 @@ def cmd_run(args) -> int:
             flops, what = 2.0 * M * N * K, "gemm_nt M=N=8192 K=%d fp16" % K
             call = lambda lib: lib.gemm_nt(a.data_ptr(), b.data_ptr(), out.data_ptr(), M, N, K, stream, 0)
             view = lambda: out.view(torch.float16)[::509, ::263].float().cpu().numpy()
+        elif op == "attn_fp8":
+            w = I.FP8_WORKLOADS[args.fp8_workload]
+            q, k, v = (torch.from_numpy(x).cuda() for x in I.make_workload(w))
+            out = torch.empty((w.B, w.H, w.N, w.d), dtype=torch.int16, device="cuda")
+            lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
+            flops, what = w.flops, w.name
+            call = lambda lib: lib.attn_fwd_fp8(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                                w.B, w.H, w.N, w.d, w.scale, int(w.causal), stream, 0)
+            view = lambda: np.concatenate([out.view(torch.float16)[:, :, ::251, ::7].float().cpu().numpy().ravel(),
+                                           lse[:, :, ::251].cpu().numpy().ravel()])
         else:
             w = I.WORKLOADS[args.causal_workload if op == "attn_causal" else args.workload]
             q, k, v = (torch.from_numpy(x.view("int16")).cuda() for x in I.make_workload(w))
@@ -162,6 +178,7 @@ def main(argv=None) -> int:
         else:
             sp.add_argument("--workload", default="c4")
             sp.add_argument("--causal-workload", default="c5")
+            sp.add_argument("--fp8-workload", default="f4")
             sp.add_argument("--K", type=int, default=16384)
             sp.add_argument("--steps", type=int, default=50)
             sp.add_argument("--warmup", type=int, default=15)
