@@ -1,33 +1,51 @@
 // Fused attention forward for gfx950 (MI355X) on 8-bit-float inputs: Q, K, V in OCP E4M3, O in
 // fp16 or bf16, per-row log-sum-exp in fp32.  The paper evaluates attention in a second precision
-// it calls FP8 (Section 5.4); the three stages per key/value tile are the same as in the 16-bit
-// kernel (Section 3.4.2: T = Q K^T, C = softmax, U = P V) and so is the pipeline: a ring of LDS
-// stages filled by direct-to-LDS copies two tiles ahead, one wait + one barrier per tile, and two
-// wave groups per workgroup that run T/U and C half a period apart so that the matrix cores of a
-// SIMD work for one wave while its vector ALU works for the other.
+// it calls FP8 (Section 5.4); the three stages per key/value tile are the ones of Section 3.4.2
+// (T = Q K^T on the matrix cores, C = softmax on the vector ALU, U = P V on the matrix cores).
+//
+// Schedule.  At this precision the vector ALU is the busier unit (the MFMA time halves, the
+// softmax does not), and a 32x32x64 MFMA on 8-bit operands occupies the matrix pipe for 64 cycles
+// while its wave is free to issue vector instructions (measured: 12 FMAs between two such MFMAs of
+// one wave cost nothing).  So the coarse-grained pipeline of the paper's Algorithm 1 lives INSIDE
+// every wave's instruction stream here: in iteration j a wave issues the MFMAs of U_{j-1} and
+// T_{j+1} and, between them, slices of the softmax C_j.  S and P are double buffered in registers
+// (tile parity), the loop is unrolled by two.  All eight waves run the same code; the two waves of
+// a SIMD fill each other's gaps on both pipes.
+//
+// Data movement.  A ring of LDS stages (four by default; a stage is 16 KiB at d = 128), filled by
+// direct-to-LDS copies (16 B per lane, no register staging) STAGES - 2 tiles ahead; one s_waitcnt +
+// one s_barrier per tile stand in for the full/empty credits of the paper's aref ring (Section
+// 3.3): a stage is overwritten only after every wave has passed the barrier that follows its last
+// read of it.  Stage s holds K tile s+2 and V tile s, the pair that iteration s+1 reads.  Barrier j
+// makes stage j visible, one stage more than iteration j reads; with ATTN8_POSTFETCH a wave then
+// requests the first LDS fragments of iteration j+1 before it waits at barrier j+1.  (Measured on
+// MI355X: a deeper ring, that early request and spreading the copies over the pass each cost
+// 1-3 %; they stay as knobs of the schedule sweep.)
 //
 // What changes with the element type:
-//  * Both contractions use the 32x32x64 MFMA on 8-bit operands (64 contraction elements per
-//    instruction, 32 bytes per lane and operand): T takes D/64 steps per 32-key block, U one step
-//    per 64 keys and 32 output features.
+//  * Both contractions use the 32x32x64 MFMA on 8-bit operands (32 bytes per lane and operand):
+//    T takes D/64 steps per 32-key block, U one step per 64 keys and 32 output features.
 //  * The probabilities are rounded to E4M3 (round to nearest even) before the second contraction.
 //    The softmax reference only moves when a row maximum grew by more than 2^8, so they stay
 //    below 2^8 < 448 and never overflow the format.
 //  * The row sum comes from the matrix cores as well: next to the D/32 feature blocks of V^T the
 //    second contraction multiplies a block of ones with the same P operand, which yields the sum
 //    of the ROUNDED probabilities of every query row (O is then an exact convex combination of the
-//    V rows) and takes the additions off the vector ALU, the busier unit at this precision.
-//  * LDS layouts (every one produced by the choice of which global address a lane copies):
-//      K tile: [16-byte column (D/16)][key (BN)][16 B]: the A operand of T (lane = key, 32
-//              consecutive features) is two 128-bit reads, 16 consecutive lanes 256 contiguous bytes.
-//      V tile: [feature group of 32 (D/32)][position (BN)][32 B], where position p holds key
-//              p ^ 4 when bit 3 of p is set: the A operand of U (lane = feature, 8 keys per read)
-//              comes from the transposing 64-bit read for 8-bit elements, whose two groups of four
-//              keys then sit in different halves of the LDS banks.
+//    V rows) and takes the additions off the vector ALU.
+//  * LDS layouts.  A key row is D bytes, at most one 128-byte memory line, so every copy
+//    instruction fetches whole rows (8 or 16 per instruction, fully coalesced) and both tiles are
+//    row-major in the LDS; only the order of the 16-byte columns inside a row is permuted (which
+//    global column a lane fetches is free, where its 16 bytes land is not):
+//      K tile: row = key, column c stored at slot c ^ swK(row): the A operand of T (lane = key, 32
+//              consecutive features = two 128-bit reads) is conflict free over 16 consecutive keys.
+//      V tile: row = position, where position p holds the key with bits 2 and 3 of p swapped, and
+//              column c stored at slot c ^ swV(p): the A operand of U (lane = feature, 8 keys per
+//              read) comes from the transposing 64-bit read for 8-bit elements; the 8 keys of a
+//              read are 8 consecutive positions, and a half-wave's 8 rows x 32 bytes cover all banks.
 //
-// Register layout: as in the 16-bit kernel the scores are computed transposed (S^T = K Q^T), a lane
-// owns one query and half of the keys of a block, the row maximum needs one lane <-> lane+32
-// exchange, and the packed probabilities already are the B operand of the second contraction.
+// Register layout: the scores are computed transposed (S^T = K Q^T), a lane owns one query and
+// half of the keys of a 32-key block, the row maximum needs one lane <-> lane+32 exchange, and the
+// packed probabilities already are the B operand of the second contraction.
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -48,25 +66,29 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 // (the largest probability then is 2^8 = 256, below the largest finite E4M3 value 448).
 constexpr float RESCALE_LOG2_FP8 = 8.0f;
 
-// LDS fragments requested ahead of their MFMA inside a burst.
+// LDS fragments requested ahead of their MFMA inside a pass.
 #ifndef ATTN8_FWIN
 #define ATTN8_FWIN 2
 #endif
 
-// Where the row sum of the probabilities is computed: 0 = on the matrix cores (a block of ones next to
-// V^T: the sum of the ROUNDED probabilities, no vector-ALU work), 1 = on the vector ALU (fp32 additions
-// of the unrounded probabilities, one per score, and one MFMA less per 64 keys).
-#ifndef ATTN8_ROWSUM_VALU
-#define ATTN8_ROWSUM_VALU 0
+// 1: the softmax of tile j is issued in slices between the MFMAs of U_{j-1} and T_{j+1} (the
+// software pipeline described above); 0: after them, as one block.
+#ifndef ATTN8_INTERLEAVE
+#define ATTN8_INTERLEAVE 1
 #endif
 
-// Block scales of the MFMA: 0 selects the plain (unscaled) instruction.
-#ifndef ATTN8_SCALE_WORD
-#define ATTN8_SCALE_WORD 0
+// 1: a pass requests the first LDS fragments of the next pass before the barrier between them; 0: after it.
+#ifndef ATTN8_POSTFETCH
+#define ATTN8_POSTFETCH 0
+#endif
+
+// 1: the copies of a stage are issued between the MFMAs of a pass, in two portions; 0: right after the barrier.
+#ifndef ATTN8_SPREAD_COPIES
+#define ATTN8_SPREAD_COPIES 0
 #endif
 
 #ifdef ATTN8_TIMING
-// Profiling builds only: per-wave cycle totals of the main-loop sections of the first workgroups.
+// Profiling builds only: cycle and wall-clock totals of the main loop of the first workgroups.
 constexpr int DBG8_WGS = 1024, DBG8_SLOTS = 8;
 __device__ unsigned long long attn8_dbg[DBG8_WGS * 8 * DBG8_SLOTS];
 #define TSTAMP8(var) unsigned long long var; __builtin_amdgcn_sched_barrier(0); \
@@ -77,8 +99,9 @@ __device__ unsigned long long attn8_dbg[DBG8_WGS * 8 * DBG8_SLOTS];
 #define TACC8(slot, a, b)
 #endif
 
+// (block scales 0, 0 select the plain, unscaled instruction)
 __device__ __forceinline__ f32x16 mfma_fp8(i32x8 a, i32x8 b, f32x16 c) {
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, ATTN8_SCALE_WORD, 0, ATTN8_SCALE_WORD);
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
 }
 
 __device__ __forceinline__ float xor32_max_fp8(float x) {
@@ -98,22 +121,22 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
                          float scale, float scale_log2e)
 {
     typedef Elem<OUT> EO;
-    constexpr int NW = 8, STAGES = 4;
+    constexpr int NW = 8, STAGES = ATTN8_STAGES;
+    constexpr int AHEAD = STAGES - 2;           // iteration j issues the copies of stage j + AHEAD
     constexpr int BM = NW * 32;                 // query rows per workgroup
     constexpr int KB = BN / 32;                 // 32-key blocks per K/V tile
     constexpr int KC = BN / 64;                 // 64-key contraction steps of U
     constexpr int FK = D / 64;                  // contraction steps of T
     constexpr int DB = D / 32;                  // 32-wide feature blocks of O
-    constexpr int ROW_BYTES = D;
-    constexpr int TILE_BYTES = BN * ROW_BYTES;  // one K or one V tile
+    constexpr int CPR = D / 16;                 // 16-byte columns per row
+    constexpr int RPB = 256 / D;                // rows per 256 bytes (one sweep over the LDS banks)
+    constexpr int RPP = 1024 / D;               // rows per 1 KiB piece (one copy instruction)
+    constexpr int TILE_BYTES = BN * D;          // one K or one V tile
     constexpr int STAGE_BYTES = 2 * TILE_BYTES;
-    constexpr int KCOL = BN * 16;               // bytes of one 16-byte column of the K tile
-    constexpr int VGRP = BN * 32;               // bytes of one feature group of the V tile
-    constexpr int CHUNKS = TILE_BYTES / 1024;   // 1 KiB wave-transfers per tile
-    constexpr int CPW = CHUNKS / NW;            // ... per wave
-    constexpr int LPG = 2 * CPW;                // copies a wave issues per stage (K part + V part)
-    static_assert(BN % 64 == 0 && D % 64 == 0, "tile shape");
-    static_assert(CHUNKS % NW == 0 && CPW >= 1, "tile must split evenly over the eight waves");
+    constexpr int CHUNKS = TILE_BYTES / 1024;   // pieces per tile
+    constexpr int PPW = 2 * CHUNKS / NW;        // pieces (of K or V) a wave copies per stage
+    static_assert(BN % 64 == 0 && (D == 64 || D == 128), "tile shape");
+    static_assert((2 * CHUNKS) % NW == 0 && PPW >= 1, "a stage must split evenly over the eight waves");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const unsigned lds_base = (unsigned)(size_t)(LDS_AS void*)smem;
@@ -121,10 +144,9 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int lr = lane & 31, g = lane >> 5;
-    const bool group_b = wave >= NW / 2;        // waves w and w + 4 share a SIMD
 
     // ---- which (batch*head, query tile) this workgroup works on
-    int tile = __builtin_amdgcn_readfirstlane(tile_schedule(total, (int)gridDim.x, (int)blockIdx.x, 0));
+    const int tile = __builtin_amdgcn_readfirstlane(tile_schedule(total, (int)gridDim.x, (int)blockIdx.x, 0));
     const int bh = __builtin_amdgcn_readfirstlane(tile / nqt);
     int qt = tile - bh * nqt;
     if (CAUSAL) qt = nqt - 1 - qt;              // long rows first
@@ -136,147 +158,145 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     const char* vh = uniform_ptr(reinterpret_cast<const char*>(v + head_off));
     int nt = (N + BN - 1) / BN;                 // K/V tiles the workgroup walks
     if (CAUSAL) nt = min(nt, (min(q0 + BM, N) - 1) / BN + 1);
-    int nt_w = nt;                              // those this wave computes on
+    int nt_w = nt;                              // those this wave computes on (1 <= nt_w <= nt)
     if (CAUSAL) nt_w = min(nt, (wq0 + 31) / BN + 1);
     nt = __builtin_amdgcn_readfirstlane(nt);
     nt_w = __builtin_amdgcn_readfirstlane(nt_w);
+    const int last_stage = max(AHEAD - 1, nt - 1);   // stages -2 .. last_stage are copied
 
-    // ---- global -> LDS copies.  Stage s of the ring holds K tile s+1 and V tile s: the pair one
-    // MFMA burst reads.  A wave moves CPW 1 KiB pieces of each; lane L's 16 bytes land at piece + 16 L.
-    // K piece = 64 keys of one 16-byte column: lane L fetches key L, that column.
-    // V piece = 32 positions of one feature group: lane L fetches position L/2, half L%2.
-    const int v_keyl = (lane >> 1) ^ ((((lane >> 1) >> 3) & 1) << 2);   // key held at position L/2
-    const unsigned k_lane_off = lane * ROW_BYTES;
-    const unsigned v_lane_off = v_keyl * ROW_BYTES + (lane & 1) * 16;
-    int k_src[CPW], v_src[CPW], k_row0[CPW], v_row0[CPW], piece_dst[CPW];   // wave-uniform
+    // ---- global -> LDS copies.  Stage s holds K tile s+2 and V tile s.  A tile is CHUNKS pieces of
+    // 1 KiB (RPP whole rows each).  With an even number of pieces per wave every wave copies as many
+    // K pieces as V pieces; with one piece per wave the first half of the waves copies K, the second V.
+    // Lane L's 16 bytes land at piece + 16 L, i.e. row L / CPR of the piece, slot L % CPR; which
+    // column of which global row it fetches follows from the layouts above.
+    constexpr bool SPLIT = PPW % 2 == 0;
+    unsigned piece_lane_off[PPW];               // per lane: byte offset of its 16 bytes inside the source tile
+    int piece_row[PPW], piece_col[PPW];         // per lane: the tile-local source row and column of the same
+    int piece_dst[PPW];                         // wave-uniform: byte offset of the piece inside the stage
+    bool piece_is_v[PPW];                       // compile-time when SPLIT, else wave-uniform
+    const char* piece_src[PPW];                 // wave-uniform: start of the tile that stage 0 takes (K tile 2 or V tile 0)
 #pragma unroll
-    for (int i = 0; i < CPW; ++i) {
-        const int wc = wave * CPW + i;
-        const int c = wc / (BN / 64), rh = wc % (BN / 64);
-        const int db = wc / (BN / 32), ph = wc % (BN / 32);
-        k_row0[i] = rh * 64;
-        k_src[i] = rh * 64 * ROW_BYTES + c * 16;
-        v_row0[i] = ph * 32;
-        v_src[i] = ph * 32 * ROW_BYTES + db * 32;
-        piece_dst[i] = wc * 1024;
+    for (int i = 0; i < PPW; ++i) {
+        int pc;                                 // piece index inside its tile
+        if (SPLIT) {
+            piece_is_v[i] = i >= PPW / 2;
+            pc = wave * (PPW / 2) + i % (PPW / 2 > 0 ? PPW / 2 : 1);
+        } else {
+            piece_is_v[i] = wave * PPW + i >= CHUNKS;
+            pc = piece_is_v[i] ? wave * PPW + i - CHUNKS : wave * PPW + i;
+        }
+        const int p = pc * RPP + lane / CPR;    // LDS row of this lane's 16 bytes
+        const int slot = lane % CPR;
+        int row, col;
+        if (piece_is_v[i]) {
+            row = (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1);          // position p holds the key with bits 2, 3 swapped
+            col = slot ^ (2 * ((p / RPB) % (CPR / 2)));
+        } else {
+            row = p;
+            col = slot ^ ((p / RPB) % CPR);
+        }
+        piece_row[i] = row;
+        piece_col[i] = col;
+        piece_lane_off[i] = row * D + col * 16;
+        piece_dst[i] = __builtin_amdgcn_readfirstlane((piece_is_v[i] ? TILE_BYTES : 0) + pc * 1024);
+        piece_src[i] = uniform_ptr(piece_is_v[i] ? vh : kh + 2 * TILE_BYTES);
     }
-    auto issue_stage = [&](int s) __attribute__((always_inline)) {             // s = -1 is the stage that only brings K tile 0
-        const unsigned sbase = lds_base + ((s + STAGES) % STAGES) * STAGE_BYTES;
-        if (s >= 0 && (s + 2) * BN <= N) {      // K tile s+1 and V tile s lie wholly inside the sequence
-            const char* kt = kh + (size_t)(s + 1) * TILE_BYTES;
-            const char* vt = vh + (size_t)s * TILE_BYTES;
+    // Stage s lies wholly inside the sequence (K tile s+2 is its last one): scalar address arithmetic only.
+    // `half`: 0 = the first half of this wave's pieces, 1 = the second half (K and V when the wave has both).
+    auto stage_inside = [&](int s) __attribute__((always_inline)) -> bool { return (s + 3) * BN <= N; };
+    auto issue_inside = [&](int s, int half) __attribute__((always_inline)) {
+        const unsigned sbase = lds_base + ((s + 2 * STAGES) % STAGES) * STAGE_BYTES;
 #pragma unroll
-            for (int i = 0; i < CPW; ++i) dma16(kt + k_src[i], k_lane_off, sbase + piece_dst[i]);
+        for (int i = 0; i < PPW; ++i)
+            if (PPW == 1 ? half == 0 : (i >= PPW / 2) == (half == 1))
+                dma16(piece_src[i] + (size_t)s * TILE_BYTES, piece_lane_off[i], sbase + piece_dst[i]);
+    };
+    // any stage: rows clamped into the sequence (surplus rows are masked or never read)
+    auto issue_stage = [&](int s) __attribute__((always_inline)) {
+        const unsigned sbase = lds_base + ((s + 2 * STAGES) % STAGES) * STAGE_BYTES;
 #pragma unroll
-            for (int i = 0; i < CPW; ++i) dma16(vt + v_src[i], v_lane_off, sbase + TILE_BYTES + piece_dst[i]);
-        } else {                                // rows clamped into the sequence (surplus rows are masked or never read)
-#pragma unroll
-            for (int i = 0; i < CPW; ++i) {
-                const int row = min(max((s + 1) * BN + k_row0[i] + lane, 0), N - 1);
-                dma16(kh, (unsigned)(row * ROW_BYTES + (k_src[i] - k_row0[i] * ROW_BYTES)), sbase + piece_dst[i]);
-            }
-#pragma unroll
-            for (int i = 0; i < CPW; ++i) {
-                const int row = min(max(s * BN + v_row0[i] + v_keyl, 0), N - 1);
-                dma16(vh, (unsigned)(row * ROW_BYTES + (v_src[i] - v_row0[i] * ROW_BYTES) + (lane & 1) * 16),
-                      sbase + TILE_BYTES + piece_dst[i]);
-            }
+        for (int i = 0; i < PPW; ++i) {
+            const int t = piece_is_v[i] ? s : s + 2;                   // the tile this piece belongs to
+            const int row = min(max(t * BN + piece_row[i], 0), N - 1);
+            dma16(piece_is_v[i] ? vh : kh, (unsigned)(row * D + piece_col[i] * 16), sbase + piece_dst[i]);
         }
     };
 
-    // ---- prologue: three stages in flight, Q fragments into registers
-    issue_stage(-1);
-    issue_stage(0);
-    issue_stage(1);
+    // ---- prologue: Q fragments into registers, then the whole ring in flight.  The Q loads are
+    // written as asm so that the compiler does not wait for them (its s_waitcnt vmcnt(0) would also
+    // wait for every copy issued after them); the wait below covers them, they were issued first.
     i32x8 Qf[FK];                               // B operand of T: query lane%32, features fk*64 + (lane/32)*32 .. +31
     {
         const int row = min(wq0 + lr, N - 1);
-        const uint8_t* qr = qh + (size_t)row * D;
+        const uint8_t* qr = qh + (size_t)row * D + g * 32;
 #pragma unroll
         for (int fk = 0; fk < FK; ++fk) {
-            const i32x4 lo = *reinterpret_cast<const i32x4*>(qr + fk * 64 + g * 32);
-            const i32x4 hi = *reinterpret_cast<const i32x4*>(qr + fk * 64 + g * 32 + 16);
+            i32x4 lo, hi;
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(lo) : "v"(qr + fk * 64) : "memory");
+            asm volatile("global_load_dwordx4 %0, %1, off offset:16" : "=&v"(hi) : "v"(qr + fk * 64) : "memory");
             Qf[fk] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         }
     }
+#pragma unroll
+    for (int s0 = -2; s0 < AHEAD; ++s0) issue_stage(s0);
 
-    f32x16 O[DB], L, S[KB];                     // L: the ones block of the second contraction = row sums
-    int pw[KB * 4];                             // P of the current tile, four E4M3 values per word
-    float m_run, l_valu = 0.f;                  // l_valu: this lane's share of the row sum when the vector ALU keeps it
+    // A operand of the ones block: 1.0 in every byte, kept in registers for the whole kernel
+    i32x8 ones;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        int w = 0x38383838;
+        asm volatile("" : "+v"(w));
+        ones[t] = w;
+    }
 
-    // per-lane LDS read offsets (the rest of every address is an immediate)
-    const int k_lane = g * 2 * KCOL + lr * 16;
-    const int v_e = (lane & 15) >> 1;           // which of the 8 key rows of a transposing read this lane addresses
-    const int v_pos = v_e < 4 ? g * 4 + v_e : 8 + (1 - g) * 4 + (v_e - 4);
-    const int v_lane = TILE_BYTES + v_pos * 32 + ((lane >> 4) & 1) * 16 + (lane & 1) * 8;
+    f32x16 O[DB], L, S[2][KB];                  // L: the ones block of the second contraction = row sums
+    int pw[2][KB * 4] = {};                     // P of two consecutive tiles, four E4M3 values per word
+    float m_run;
 
-    // K fragment (A operand of T): key kb*32 + lane%32, features fk*64 + (lane/32)*32 .. +31
-    auto read_kf = [&](const char* sk, int kb, int fk) __attribute__((always_inline)) -> i32x8 {
-        const char* a = sk + fk * 4 * KCOL + kb * 512;
-        const i32x4 lo = *reinterpret_cast<const i32x4*>(a);
-        const i32x4 hi = *reinterpret_cast<const i32x4*>(a + KCOL);
+    // ---- per-lane LDS read offsets (the rest of every address is an immediate)
+    // K fragment (A operand of T): key kb*32 + lane%32, features fk*64 + (lane/32)*32 .. +31 = columns
+    // fk*4 + g*2 and the next one, each at its permuted slot.
+    int k_lane[FK][2];
+#pragma unroll
+    for (int fk = 0; fk < FK; ++fk)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            k_lane[fk][h] = lr * D + (((fk * 4 + g * 2 + h) ^ ((lr / RPB) % CPR)) * 16);
+    // V^T fragment (A operand of U): feature db*32 + lane%32; a transposing read hands lane i of a
+    // 16-lane group byte i of the 8 rows that the group's lane pairs (2e, 2e+1) address.  The rows
+    // are positions 16 r + 8 g + e, which hold the keys of P words 2r and 2r+1 of this lane group.
+    int v_lane[DB];
+    {
+        const int e = (lane & 15) >> 1, fh = (lane >> 4) & 1;
+        const int p = g * 8 + e;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            v_lane[db] = TILE_BYTES + p * D + (((db * 2 + fh) ^ (2 * ((p / RPB) % (CPR / 2)))) * 16) + (lane & 1) * 8;
+    }
+    auto read_kf = [&](const char* st, int kb, int fk) __attribute__((always_inline)) -> i32x8 {
+        const i32x4 lo = *reinterpret_cast<const i32x4*>(st + k_lane[fk][0] + kb * 32 * D);
+        const i32x4 hi = *reinterpret_cast<const i32x4*>(st + k_lane[fk][1] + kb * 32 * D);
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
-    // V^T fragment (A operand of U): feature db*32 + lane%32, the 32 keys of chunk kc that the P words
-    // of this lane group hold, in the order of those words: four transposing reads of 8 keys each
-    auto read_vf = [&](const char* sv, int kc, int db) __attribute__((always_inline)) -> i32x8 {
-        const char* a = sv + db * VGRP + kc * 64 * 32;
+    auto read_vf = [&](const char* st, int kc, int db) __attribute__((always_inline)) -> i32x8 {
+        const char* a = st + v_lane[db] + kc * 64 * D;
         const i32x2 r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a));
-        const i32x2 r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a + 16 * 32));
-        const i32x2 r2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a + 32 * 32));
-        const i32x2 r3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a + 48 * 32));
+        const i32x2 r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a + 16 * D));
+        const i32x2 r2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a + 32 * D));
+        const i32x2 r3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a + 48 * D));
         const i32x4 lo = __builtin_shufflevector(r0, r1, 0, 1, 2, 3);
         const i32x4 hi = __builtin_shufflevector(r2, r3, 0, 1, 2, 3);
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
-    // ---- MFMA burst on one stage: U (O^T += V^T P^T and the ones block, with the P in pw) and/or
-    // T (S^T = K Q^T), as one stream of MFMAs whose LDS fragments are requested FWIN MFMAs ahead.
-    auto mfma_burst = [&](auto do_u, auto do_t, const char* stage_ptr) __attribute__((always_inline)) {
-        constexpr int UB = ATTN8_ROWSUM_VALU ? DB : DB + 1;             // per chunk: DB feature blocks, then the ones block
-        constexpr int NU = decltype(do_u)::value ? KC * UB : 0;
-        constexpr int NT = decltype(do_t)::value ? KB * FK : 0;
-        constexpr int NF = NU + NT;
-        constexpr int FWIN = ATTN8_FWIN < NF ? ATTN8_FWIN : NF;
-        const char* sk = stage_ptr + k_lane;
-        const char* sv = stage_ptr + v_lane;
-        i32x8 fr[NF];
-        auto fetch = [&](int f) __attribute__((always_inline)) {
-            if (f < NU) {
-                const int kc = f / UB, db = f % UB;
-                if (db < DB) fr[f] = read_vf(sv, kc, db);
-                else fr[f] = i32x8(0x38383838);                         // 1.0 in every byte
-            } else {
-                fr[f] = read_kf(sk, (f - NU) % KB, (f - NU) / KB);
-            }
-        };
-        auto run_mfma = [&](int f) __attribute__((always_inline)) {
-            if (f < NU) {
-                const int kc = f / UB, db = f % UB;
-                i32x8 p;
-#pragma unroll
-                for (int t = 0; t < 8; ++t) p[t] = pw[kc * 8 + t];
-                if (db < DB) O[db] = mfma_fp8(fr[f], p, O[db]);
-                else L = mfma_fp8(fr[f], p, L);
-            } else {
-                const int kb = (f - NU) % KB, fk = (f - NU) / KB;
-                S[kb] = mfma_fp8(fr[f], Qf[fk], fk == 0 ? f32x16(0.f) : S[kb]);
-            }
-        };
-#pragma unroll
-        for (int f = 0; f < FWIN; ++f) fetch(f);
-#pragma unroll
-        for (int f = 0; f < NF; ++f) {
-            if (f + FWIN < NF) fetch(f + FWIN);
-            run_mfma(f);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-
-    // ---- C of tile j: mask, streaming softmax of S into pw (E4M3), running maximum, rescaling of O and L.
-    auto softmax_tile = [&](int j) __attribute__((always_inline)) {
-        const int kv0 = j * BN;
-        if ((kv0 + BN > N) || (CAUSAL && kv0 + BN - 1 > wq0)) {
+    // ---- softmax state shared by the slices of one tile
+    float sm_alpha = 1.f, sm_negmc = 0.f;
+    bool sm_upd = false;
+    // first slice: (mask,) row maximum, reference update, rescaling factor
+    auto softmax_head = [&](auto par, auto masked, int j) __attribute__((always_inline)) {
+        constexpr int P = decltype(par)::value;
+        if (decltype(masked)::value) {
+            const int kv0 = j * BN;
             const int qi = wq0 + lr;
             const int lim = CAUSAL ? min(qi, N - 1) : N - 1;   // last visible key
 #pragma unroll
@@ -284,62 +304,236 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int key = kv0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-                    if (key > lim) S[kb][i] = -__builtin_inff();
+                    if (key > lim) S[P][kb][i] = -__builtin_inff();
                 }
         }
-        float mx = S[0][0];
+        float mx = S[P][0][0];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) mx = __builtin_fmaxf(mx, S[kb][i]);
+            for (int i = 0; i < 16; ++i) mx = __builtin_fmaxf(mx, S[P][kb][i]);
         mx = xor32_max_fp8(mx);
         const float m_old = m_run;
         const float m_new = __builtin_fmaxf(m_old, mx);
-        const bool upd = (m_new - m_old) * scale_log2e > RESCALE_LOG2_FP8;
-        const float m_use = upd ? m_new : m_old;
-        const float alpha = __builtin_amdgcn_exp2f((m_old - m_use) * scale_log2e);
-        const float neg_mc = -m_use * scale_log2e;
+        sm_upd = (m_new - m_old) * scale_log2e > RESCALE_LOG2_FP8;
+        const float m_use = sm_upd ? m_new : m_old;
+        sm_alpha = __builtin_amdgcn_exp2f((m_old - m_use) * scale_log2e);
+        sm_negmc = -m_use * scale_log2e;
         m_run = m_use;
-        float sum[4] = {0.f, 0.f, 0.f, 0.f};
+    };
+    // slice g4 of KB*4: four scores -> one word of E4M3 probabilities
+    auto softmax_group = [&](auto par, int g4) __attribute__((always_inline)) {
+        constexpr int P = decltype(par)::value;
+        const int kb = g4 / 4, t = g4 % 4;
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[P][kb][4 * t + 0], scale_log2e, sm_negmc));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[P][kb][4 * t + 1], scale_log2e, sm_negmc));
+        const float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[P][kb][4 * t + 2], scale_log2e, sm_negmc));
+        const float p3 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[P][kb][4 * t + 3], scale_log2e, sm_negmc));
+        // (the first conversion fills the low half of the word and keeps the rest, the second fills the
+        // high half: starting from the word's previous content saves clearing a register)
+        int w = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, pw[P][kb * 4 + t], false);
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(p2, p3, w, true);
+        // (pins the slice where it is written: the word is only used by the next pass, and the
+        // compiler would otherwise sink the whole slice down to that use)
+        asm volatile("" : "+v"(w));
+        pw[P][kb * 4 + t] = w;
+    };
+    // after the U of the previous tile: move O and L to the new reference (rare after the first tiles)
+    auto softmax_rescale = [&]() __attribute__((always_inline)) {
+        if (__builtin_amdgcn_ballot_w64(sm_upd) != 0) {
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][4 * t + 0], scale_log2e, neg_mc));
-                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][4 * t + 1], scale_log2e, neg_mc));
-                const float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][4 * t + 2], scale_log2e, neg_mc));
-                const float p3 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][4 * t + 3], scale_log2e, neg_mc));
-                int w = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, 0, false);
-                w = __builtin_amdgcn_cvt_pk_fp8_f32(p2, p3, w, true);
-                pw[kb * 4 + t] = w;
-                if (ATTN8_ROWSUM_VALU) { sum[0] += p0; sum[1] += p1; sum[2] += p2; sum[3] += p3; }
-            }
-        if (ATTN8_ROWSUM_VALU) l_valu = l_valu * alpha + ((sum[0] + sum[1]) + (sum[2] + sum[3]));
-        if (__builtin_amdgcn_ballot_w64(upd) != 0) {
-#pragma unroll
-            for (int db = 0; db < DB; ++db) O[db] = O[db] * alpha;
-            L = L * alpha;
+            for (int db = 0; db < DB; ++db) O[db] = O[db] * sm_alpha;
+            L = L * sm_alpha;
         }
     };
 
-    // At barrier j every wave's share of stages <= j has landed and nobody reads stage j-2 any more,
-    // so that stage takes the copies of stage j+2.
-    auto wait_stage = [&](int j) __attribute__((always_inline)) {
-        if (j + 1 < nt) wait_vmcnt<LPG>(); else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
+    // ---- one pass over a stage: the MFMAs of U (O^T += V^T P^T and the ones block, P of parity
+    // PAR^1) and/or T (S^T of parity PAR^1 = K Q^T), LDS fragments requested FWIN MFMAs ahead, and,
+    // between the MFMAs, the softmax of the scores of parity PAR (tile j).  The scheduling
+    // barriers keep that order.  PRE: the first FWIN fragments were requested at the end of the
+    // previous pass (they sit in `carry`); POST: request those of the next pass, from st_next.
+    // issue_s: the stage whose copies this pass issues between its MFMAs, spread over two points so
+    // that the eight waves do not all queue at the copy unit right after the barrier (< -2: none).
+    constexpr int FWIN_MAX = ATTN8_FWIN < DB ? ATTN8_FWIN : DB;
+    i32x8 carry[FWIN_MAX];
+    auto pass = [&](auto do_u, auto do_t, auto do_c, auto pre, auto post, auto par, const char* st, const char* st_next,
+                    int j, int issue_s) __attribute__((always_inline)) {
+        constexpr int P = decltype(par)::value;
+        constexpr bool C = decltype(do_c)::value;
+        constexpr int UB = DB + 1;                                      // per 64 keys: DB feature blocks, then the ones block
+        constexpr int NU = decltype(do_u)::value ? KC * UB : 0;
+        constexpr int NT = decltype(do_t)::value ? KB * FK : 0;
+        constexpr int NF = NU + NT;
+        constexpr int FWIN = FWIN_MAX < NF ? FWIN_MAX : NF;
+        constexpr int NG = KB * 4;                                      // softmax slices after the head
+        constexpr bool IL = C && ATTN8_INTERLEAVE && NF >= 2;
+        constexpr int H1 = NF / 4, H2 = (3 * NF) / 4;                   // after these MFMAs the copies are issued
+        static_assert(!decltype(pre)::value || (NU >= FWIN_MAX && FWIN == FWIN_MAX), "carried fragments are the first ones of U");
+        i32x8 fr[NF > 0 ? NF : 1];
+        auto fetch = [&](int f) __attribute__((always_inline)) {
+            if (f < NU) {
+                const int kc = f / UB, db = f % UB;
+                if (db < DB) fr[f] = read_vf(st, kc, db);
+                else fr[f] = ones;
+            } else {
+                fr[f] = read_kf(st, (f - NU) % KB, (f - NU) / KB);
+            }
+        };
+        auto run_mfma = [&](int f) __attribute__((always_inline)) {
+            if (f < NU) {
+                const int kc = f / UB, db = f % UB;
+                i32x8 p;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) p[t] = pw[P ^ 1][kc * 8 + t];
+                if (db < DB) O[db] = mfma_fp8(fr[f], p, O[db]);
+                else L = mfma_fp8(fr[f], p, L);
+            } else {
+                const int kb = (f - NU) % KB, fk = (f - NU) / KB;
+                S[P ^ 1][kb] = mfma_fp8(fr[f], Qf[fk], fk == 0 ? f32x16(0.f) : S[P ^ 1][kb]);
+            }
+        };
+#pragma unroll
+        for (int f = 0; f < FWIN; ++f) {
+            if (decltype(pre)::value && ATTN8_POSTFETCH) fr[f] = carry[f]; else fetch(f);
+        }
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            if (f + FWIN < NF) fetch(f + FWIN);
+            run_mfma(f);
+            __builtin_amdgcn_sched_barrier(0);
+            if (IL) {
+                if (f == 0) {
+                    softmax_head(par, std::false_type{}, j);
+                } else {
+                    // slices (f-1)*NG/(NF-1) .. f*NG/(NF-1) - 1 (rounded up), so that the last MFMA takes the last slice
+#pragma unroll
+                    for (int s = ((f - 1) * NG + NF - 2) / (NF - 1); s < (f * NG + NF - 2) / (NF - 1); ++s) softmax_group(par, s);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (ATTN8_SPREAD_COPIES && f == H1 && issue_s >= -2) {
+                if (stage_inside(issue_s)) issue_inside(issue_s, 0); else issue_stage(issue_s);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (ATTN8_SPREAD_COPIES && f == H2 && H2 != H1 && issue_s >= -2 && PPW > 1) {
+                if (stage_inside(issue_s)) issue_inside(issue_s, 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (ATTN8_SPREAD_COPIES && H2 == H1 && issue_s >= -2 && PPW > 1 && stage_inside(issue_s)) issue_inside(issue_s, 1);
+        if (decltype(post)::value && ATTN8_POSTFETCH) {
+            // the first fragments of the next pass (the V^T fragments of its U), before the barrier
+#pragma unroll
+            for (int f = 0; f < FWIN_MAX; ++f) carry[f] = read_vf(st_next, f / UB, f % UB);
+        }
+        if (C && !IL) {
+            softmax_head(par, std::false_type{}, j);
+#pragma unroll
+            for (int s = 0; s < NG; ++s) softmax_group(par, s);
+        }
+        if (C) softmax_rescale();
     };
-    auto stage_ptr = [&](int s) __attribute__((always_inline)) -> const char* { return smem + ((s + STAGES) % STAGES) * STAGE_BYTES; };
+
+    // Barrier j: every wave's share of the stages up to j has landed (the copies of the stages after
+    // it, at most AHEAD - 1 of them, may still be in flight) and nobody reads stage j-2 any more, so
+    // that slot takes the copies of stage j + AHEAD.  Returns that stage if it exists (else -3);
+    // with `now` the copies are issued here, otherwise the following pass issues them.
+#ifdef ATTN8_TIMING
+    unsigned long long dbg_acc[DBG8_SLOTS] = {};
+#endif
+    auto step = [&](int j, bool now) __attribute__((always_inline)) -> int {
+        TSTAMP8(t0);
+        const int n_out = min(j + AHEAD - 1, last_stage) - j;           // stages that may stay in flight
+        if (n_out >= AHEAD - 1) wait_vmcnt<(AHEAD - 1) * PPW>();
+        else if (n_out == 4 && AHEAD > 5) wait_vmcnt<4 * PPW>();
+        else if (n_out == 3 && AHEAD > 4) wait_vmcnt<3 * PPW>();
+        else if (n_out == 2 && AHEAD > 3) wait_vmcnt<2 * PPW>();
+        else if (n_out == 1 && AHEAD > 2) wait_vmcnt<1 * PPW>();
+        else wait_vmcnt<0>();
+        TSTAMP8(t1);
+        __builtin_amdgcn_s_barrier();
+        TSTAMP8(t2);
+        const int s = j + AHEAD <= last_stage ? j + AHEAD : -3;
+        if ((now || !ATTN8_SPREAD_COPIES) && s >= -2) {
+            if (stage_inside(s)) { issue_inside(s, 0); if (PPW > 1) issue_inside(s, 1); }
+            else issue_stage(s);
+        }
+        TACC8(0, t0, t1); TACC8(1, t1, t2);
+        return s;
+    };
+    auto stage_ptr = [&](int s) __attribute__((always_inline)) -> const char* { return smem + ((s + 2 * STAGES) % STAGES) * STAGE_BYTES; };
+
+    // The Q fragments and the stages up to 0 (everything issued before the last AHEAD - 1 stages).
+    wait_vmcnt<(AHEAD - 1) * PPW>();
+    // (tell the compiler that the Q registers are written by now; word by word: the host pass of the
+    // compiler silently drops a kernel whose inline asm takes a 256-bit operand)
+#pragma unroll
+    for (int fk = 0; fk < FK; ++fk)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(Qf[fk][t]));
+    m_run = -__builtin_inff();
+    L = f32x16(0.f);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) O[db] = f32x16(0.f);
+    __builtin_amdgcn_s_barrier();               // stages -2 .. 0 are complete for every wave
+#ifdef ATTN8_TIMING
+    const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime(), ct0 = __builtin_readcyclecounter();
+#endif
+
+    constexpr std::integral_constant<int, 0> P0{};
+    constexpr std::integral_constant<int, 1> P1{};
+    constexpr std::true_type Y{};
+    constexpr std::false_type NO{};
+
+    // Iteration j of a wave (after barrier j; it reads stage j-1 = K tile j+1, V tile j-1, and at its
+    // end the first fragments of stage j):
+    //   j <= nt_w - 2   MFMAs of U_{j-1} and T_{j+1}, softmax C_j in between (no tile before the last needs a mask)
+    //   j == nt_w - 1   U_{j-1}, then C_j with the mask (diagonal or ragged end), then U_j (stage j is visible)
+    //   j >= nt_w       nothing: the wave only keeps copying its share for the others
+    pass(NO, Y, NO, NO, NO, P1, stage_ptr(-2), nullptr, 0, -3);         // T_0 into the scores of parity 0
+    int j = 0;
+    if (nt_w >= 2) {
+        int is = step(0, false);
+        pass(NO, Y, Y, NO, Y, P0, stage_ptr(-1), stage_ptr(0), 0, is);  // T_1 and C_0
+        j = 1;
+        if (j + 1 <= nt_w - 2) {
+            do {                                // bottom-tested: the accumulators are updated in place
+                is = step(j, false);
+                pass(Y, Y, Y, Y, Y, P1, stage_ptr(j - 1), stage_ptr(j), j, is);
+                is = step(j + 1, false);
+                pass(Y, Y, Y, Y, Y, P0, stage_ptr(j), stage_ptr(j + 1), j + 1, is);
+                j += 2;
+            } while (j + 1 <= nt_w - 2);
+        }
+        if (j <= nt_w - 2) {
+            is = step(j, false);
+            pass(Y, Y, Y, Y, Y, P1, stage_ptr(j - 1), stage_ptr(j), j, is);
+            ++j;
+        }
+    }
+    // j == nt_w - 1: the last tile this wave computes on
+    auto tail = [&](auto par, auto parx) __attribute__((always_inline)) {
+        step(j, true);
+        if (j >= 1) pass(Y, NO, NO, Y, NO, par, stage_ptr(j - 1), nullptr, j, -3);     // U_{j-1}
+        softmax_head(par, Y, j);
+        __builtin_amdgcn_sched_barrier(0);      // (slice by slice: scheduled as one block this part spills registers)
+#pragma unroll
+        for (int s = 0; s < KB * 4; ++s) {
+            softmax_group(par, s);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        softmax_rescale();
+        pass(Y, NO, NO, NO, NO, parx, stage_ptr(j), nullptr, j + 1, -3);               // U_j
+    };
+    if (j & 1) tail(P1, P0); else tail(P0, P1);
+    for (++j; j < nt; ++j) step(j, true);                               // idle tail of a causal wave
+    wait_vmcnt<0>();
 
     // ---- epilogue: normalise, write O (16-bit) and LSE (natural log)
-    auto epilogue = [&]() __attribute__((always_inline)) {
+    {
         uint16_t* oh = o + head_off;
         float* lh = lse + (size_t)bh * N;
-        float l_tot = L[0];                     // every element of the ones block holds the row sum
-        if (ATTN8_ROWSUM_VALU) {                // the two lanes of a query hold half of the keys each
-            float a = l_valu, b = l_valu;
-            asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-            l_tot = a + b;
-        }
+        const float l_tot = L[0];               // every element of the ones block holds the row sum
         const float inv = 1.0f / l_tot;
         const int row = wq0 + lr;
         if (row < N) {
@@ -355,90 +549,14 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
                     *reinterpret_cast<u32x2*>(orow + db * 32 + i4 * 8 + g * 4) = w;
                 }
         }
-    };
-
-    // Use the Q fragments once here: the compiler then waits for their loads before the loop instead
-    // of inside it.  (The Q loads were issued after the copies of the prologue, so this wait also
-    // covers stages -1, 0, 1.)  Word by word: the host pass of the compiler silently drops a kernel whose
-    // inline asm takes a 256-bit operand.
-#pragma unroll
-    for (int fk = 0; fk < FK; ++fk)
-#pragma unroll
-        for (int t = 0; t < 8; ++t) asm volatile("" :: "v"(Qf[fk][t]));
-    wait_vmcnt<0>();
-    m_run = -__builtin_inff();
-    L = f32x16(0.f);
-#pragma unroll
-    for (int db = 0; db < DB; ++db) O[db] = f32x16(0.f);
-    __builtin_amdgcn_s_barrier();               // stages -1, 0, 1 are complete for every wave
-#ifdef ATTN8_TIMING
-    unsigned long long dbg_acc[DBG8_SLOTS] = {};
-    const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime(), ct0 = __builtin_readcyclecounter();
-#endif
-
-    if (!group_b) {
-        // group A, iteration j: [U_{j-1}, T_j] then C_j; both contractions read stage j-1
-        wait_stage(0);
-        mfma_burst(std::false_type{}, std::true_type{}, stage_ptr(-1));                  // T_0
-        if (2 < nt) issue_stage(2);
-        softmax_tile(0);
-        int j = 1;
-        if (j < nt_w) {
-            do {                                // bottom-tested: the accumulators are updated in place
-                TSTAMP8(t0);
-                wait_stage(j);
-                TSTAMP8(t1);
-                mfma_burst(std::true_type{}, std::true_type{}, stage_ptr(j - 1));
-                TSTAMP8(t2);
-                if (j + 2 < nt) issue_stage(j + 2);
-                TSTAMP8(t3);
-                softmax_tile(j);
-                TSTAMP8(t4);
-                TACC8(0, t0, t1); TACC8(1, t1, t2); TACC8(2, t2, t3); TACC8(3, t3, t4);
-            } while (++j < nt_w);
-        }
-        if (j < nt) wait_stage(j);                                                       // j == nt_w
-        mfma_burst(std::true_type{}, std::false_type{}, stage_ptr(j - 1));               // U of the last tile
-        if (j < nt && j + 2 < nt) issue_stage(j + 2);
-        for (++j; j < nt; ++j) {                                                         // idle tail of a causal wave
-            wait_stage(j);
-            if (j + 2 < nt) issue_stage(j + 2);
-        }
-        epilogue();
-    } else {
-        // group B, iteration j: C_j then [U_j, T_{j+1}]; both contractions read stage j
-        mfma_burst(std::false_type{}, std::true_type{}, stage_ptr(-1));                  // T_0
-        int j = 0;
-        if (j + 1 < nt_w) {
-            do {
-                TSTAMP8(t0);
-                wait_stage(j);
-                TSTAMP8(t1);
-                if (j + 2 < nt) issue_stage(j + 2);
-                TSTAMP8(t2);
-                softmax_tile(j);
-                TSTAMP8(t3);
-                mfma_burst(std::true_type{}, std::true_type{}, stage_ptr(j));
-                TSTAMP8(t4);
-                TACC8(0, t0, t1); TACC8(2, t1, t2); TACC8(3, t2, t3); TACC8(1, t3, t4);
-            } while (++j + 1 < nt_w);
-        }
-        wait_stage(j);                                                                   // j == nt_w - 1
-        if (j + 2 < nt) issue_stage(j + 2);
-        softmax_tile(j);
-        mfma_burst(std::true_type{}, std::false_type{}, stage_ptr(j));                   // U of the last tile
-        for (++j; j < nt; ++j) {                                                         // idle tail of a causal wave
-            wait_stage(j);
-            if (j + 2 < nt) issue_stage(j + 2);
-        }
-        epilogue();
     }
 #ifdef ATTN8_TIMING
     if (blockIdx.x < DBG8_WGS && lane == 0) {
-        dbg_acc[5] = nt;
-        dbg_acc[6] = __builtin_amdgcn_s_memrealtime() - rt0;   // 100 MHz ticks
-        dbg_acc[7] = __builtin_readcyclecounter() - ct0;
-        for (int i = 0; i < DBG8_SLOTS; ++i) attn8_dbg[(blockIdx.x * 8 + wave) * DBG8_SLOTS + i] = dbg_acc[i];
+        unsigned long long* d = attn8_dbg + (blockIdx.x * 8 + wave) * DBG8_SLOTS;
+        d[0] = dbg_acc[0]; d[1] = dbg_acc[1];                      // copy wait, barrier wait
+        d[5] = nt;
+        d[6] = __builtin_amdgcn_s_memrealtime() - rt0;   // 100 MHz ticks
+        d[7] = __builtin_readcyclecounter() - ct0;
     }
 #endif
 }
@@ -456,7 +574,7 @@ template <int OUT, int D, int BN, bool CAUSAL>
 int launch_fp8(const AttnLaunchArgs& a)
 {
     constexpr int BM = 256;
-    constexpr int smem = 4 * 2 * BN * D;
+    constexpr int smem = ATTN8_STAGES * 2 * BN * D;
     auto kern = attn_fwd_fp8_kernel<OUT, D, BN, CAUSAL>;
     static bool attr_set = false;   // idempotent; a race only repeats the call
     if (!attr_set) {
@@ -502,7 +620,7 @@ int attn_fp8_launch_tile_param(int d, int which)
     switch (which) {
         case 0: return 256;
         case 1: return d == 128 ? ATTN8_CFG_BN_D128 : ATTN8_CFG_BN_D64;
-        case 2: return 4;
+        case 2: return ATTN8_STAGES;
         case 3: return 512;
         default: return -1;
     }

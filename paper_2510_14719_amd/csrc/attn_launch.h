@@ -20,10 +20,15 @@
 
 // Keys per K/V tile of the 8-bit-float kernel, by head dimension.
 #ifndef ATTN8_CFG_BN_D128
-#define ATTN8_CFG_BN_D128 128
+#define ATTN8_CFG_BN_D128 64
 #endif
 #ifndef ATTN8_CFG_BN_D64
-#define ATTN8_CFG_BN_D64 128
+#define ATTN8_CFG_BN_D64 64
+#endif
+
+// LDS ring depth of the 8-bit-float kernel (a stage is 2 x BN x d bytes; 160 KiB per workgroup at most).
+#ifndef ATTN8_STAGES
+#define ATTN8_STAGES 4
 #endif
 
 struct AttnLaunchArgs {
