@@ -17,10 +17,9 @@
 // one s_barrier per tile stand in for the full/empty credits of the paper's aref ring (Section
 // 3.3): a stage is overwritten only after every wave has passed the barrier that follows its last
 // read of it.  Stage s holds K tile s+2 and V tile s, the pair that iteration s+1 reads.  Barrier j
-// makes stage j visible, one stage more than iteration j reads; with ATTN8_POSTFETCH a wave then
-// requests the first LDS fragments of iteration j+1 before it waits at barrier j+1.  (Measured on
-// MI355X: a deeper ring, that early request and spreading the copies over the pass each cost
-// 1-3 %; they stay as knobs of the schedule sweep.)
+// makes stage j visible, one stage more than iteration j reads, so the last tile's U needs no
+// barrier of its own.  (Measured on MI355X: a deeper ring, requesting the next tile's first
+// fragments before the barrier, and spreading the copies over the pass each cost 1-3 %.)
 //
 // What changes with the element type:
 //  * Both contractions use the 32x32x64 MFMA on 8-bit operands (32 bytes per lane and operand):
@@ -77,26 +76,10 @@ constexpr float RESCALE_LOG2_FP8 = 8.0f;
 #define ATTN8_INTERLEAVE 1
 #endif
 
-// 1: a pass requests the first LDS fragments of the next pass before the barrier between them; 0: after it.
-#ifndef ATTN8_POSTFETCH
-#define ATTN8_POSTFETCH 0
-#endif
-
-// 1: the copies of a stage are issued between the MFMAs of a pass, in two portions; 0: right after the barrier.
-#ifndef ATTN8_SPREAD_COPIES
-#define ATTN8_SPREAD_COPIES 0
-#endif
-
 #ifdef ATTN8_TIMING
 // Profiling builds only: cycle and wall-clock totals of the main loop of the first workgroups.
 constexpr int DBG8_WGS = 1024, DBG8_SLOTS = 8;
 __device__ unsigned long long attn8_dbg[DBG8_WGS * 8 * DBG8_SLOTS];
-#define TSTAMP8(var) unsigned long long var; __builtin_amdgcn_sched_barrier(0); \
-    asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(var) :: "memory"); __builtin_amdgcn_sched_barrier(0)
-#define TACC8(slot, a, b) dbg_acc[slot] += (b) - (a)
-#else
-#define TSTAMP8(var)
-#define TACC8(slot, a, b)
 #endif
 
 // (block scales 0, 0 select the plain, unscaled instruction)
@@ -202,14 +185,12 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         piece_src[i] = uniform_ptr(piece_is_v[i] ? vh : kh + 2 * TILE_BYTES);
     }
     // Stage s lies wholly inside the sequence (K tile s+2 is its last one): scalar address arithmetic only.
-    // `half`: 0 = the first half of this wave's pieces, 1 = the second half (K and V when the wave has both).
     auto stage_inside = [&](int s) __attribute__((always_inline)) -> bool { return (s + 3) * BN <= N; };
-    auto issue_inside = [&](int s, int half) __attribute__((always_inline)) {
+    auto issue_inside = [&](int s) __attribute__((always_inline)) {
         const unsigned sbase = lds_base + ((s + 2 * STAGES) % STAGES) * STAGE_BYTES;
 #pragma unroll
         for (int i = 0; i < PPW; ++i)
-            if (PPW == 1 ? half == 0 : (i >= PPW / 2) == (half == 1))
-                dma16(piece_src[i] + (size_t)s * TILE_BYTES, piece_lane_off[i], sbase + piece_dst[i]);
+            dma16(piece_src[i] + (size_t)s * TILE_BYTES, piece_lane_off[i], sbase + piece_dst[i]);
     };
     // any stage: rows clamped into the sequence (surplus rows are masked or never read)
     auto issue_stage = [&](int s) __attribute__((always_inline)) {
@@ -347,33 +328,27 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         }
     };
 
-    // ---- one pass over a stage: the MFMAs of U (O^T += V^T P^T and the ones block, P of parity
+    // ---- one pass over a stage: the MFMAs of U (the ones block and O^T += V^T P^T, P of parity
     // PAR^1) and/or T (S^T of parity PAR^1 = K Q^T), LDS fragments requested FWIN MFMAs ahead, and,
-    // between the MFMAs, the softmax of the scores of parity PAR (tile j).  The scheduling
-    // barriers keep that order.  PRE: the first FWIN fragments were requested at the end of the
-    // previous pass (they sit in `carry`); POST: request those of the next pass, from st_next.
-    // issue_s: the stage whose copies this pass issues between its MFMAs, spread over two points so
-    // that the eight waves do not all queue at the copy unit right after the barrier (< -2: none).
-    constexpr int FWIN_MAX = ATTN8_FWIN < DB ? ATTN8_FWIN : DB;
-    i32x8 carry[FWIN_MAX];
-    auto pass = [&](auto do_u, auto do_t, auto do_c, auto pre, auto post, auto par, const char* st, const char* st_next,
-                    int j, int issue_s) __attribute__((always_inline)) {
+    // between the MFMAs, the softmax of the scores of parity PAR (tile j): the row maximum after the
+    // first MFMA, then one slice of scores after each of the others.  The scheduling barriers keep
+    // that order.  (Measured: the row maximum before the first MFMA, the ones block first, or the
+    // maximum in four independent chains each change the time by 1-3 % the wrong way.)
+    auto pass = [&](auto do_u, auto do_t, auto do_c, auto par, const char* st, int j) __attribute__((always_inline)) {
         constexpr int P = decltype(par)::value;
         constexpr bool C = decltype(do_c)::value;
         constexpr int UB = DB + 1;                                      // per 64 keys: DB feature blocks, then the ones block
         constexpr int NU = decltype(do_u)::value ? KC * UB : 0;
         constexpr int NT = decltype(do_t)::value ? KB * FK : 0;
         constexpr int NF = NU + NT;
-        constexpr int FWIN = FWIN_MAX < NF ? FWIN_MAX : NF;
+        constexpr int FWIN = ATTN8_FWIN < NF ? ATTN8_FWIN : NF;
         constexpr int NG = KB * 4;                                      // softmax slices after the head
         constexpr bool IL = C && ATTN8_INTERLEAVE && NF >= 2;
-        constexpr int H1 = NF / 4, H2 = (3 * NF) / 4;                   // after these MFMAs the copies are issued
-        static_assert(!decltype(pre)::value || (NU >= FWIN_MAX && FWIN == FWIN_MAX), "carried fragments are the first ones of U");
         i32x8 fr[NF > 0 ? NF : 1];
         auto fetch = [&](int f) __attribute__((always_inline)) {
             if (f < NU) {
-                const int kc = f / UB, db = f % UB;
-                if (db < DB) fr[f] = read_vf(st, kc, db);
+                const int kc = f / UB, db = (f % UB) == DB ? -1 : f % UB;
+                if (db >= 0) fr[f] = read_vf(st, kc, db);
                 else fr[f] = ones;
             } else {
                 fr[f] = read_kf(st, (f - NU) % KB, (f - NU) / KB);
@@ -381,11 +356,11 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         };
         auto run_mfma = [&](int f) __attribute__((always_inline)) {
             if (f < NU) {
-                const int kc = f / UB, db = f % UB;
+                const int kc = f / UB, db = (f % UB) == DB ? -1 : f % UB;
                 i32x8 p;
 #pragma unroll
                 for (int t = 0; t < 8; ++t) p[t] = pw[P ^ 1][kc * 8 + t];
-                if (db < DB) O[db] = mfma_fp8(fr[f], p, O[db]);
+                if (db >= 0) O[db] = mfma_fp8(fr[f], p, O[db]);
                 else L = mfma_fp8(fr[f], p, L);
             } else {
                 const int kb = (f - NU) % KB, fk = (f - NU) / KB;
@@ -393,9 +368,7 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
             }
         };
 #pragma unroll
-        for (int f = 0; f < FWIN; ++f) {
-            if (decltype(pre)::value && ATTN8_POSTFETCH) fr[f] = carry[f]; else fetch(f);
-        }
+        for (int f = 0; f < FWIN; ++f) fetch(f);
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
             if (f + FWIN < NF) fetch(f + FWIN);
@@ -411,20 +384,6 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (ATTN8_SPREAD_COPIES && f == H1 && issue_s >= -2) {
-                if (stage_inside(issue_s)) issue_inside(issue_s, 0); else issue_stage(issue_s);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            if (ATTN8_SPREAD_COPIES && f == H2 && H2 != H1 && issue_s >= -2 && PPW > 1) {
-                if (stage_inside(issue_s)) issue_inside(issue_s, 1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        if (ATTN8_SPREAD_COPIES && H2 == H1 && issue_s >= -2 && PPW > 1 && stage_inside(issue_s)) issue_inside(issue_s, 1);
-        if (decltype(post)::value && ATTN8_POSTFETCH) {
-            // the first fragments of the next pass (the V^T fragments of its U), before the barrier
-#pragma unroll
-            for (int f = 0; f < FWIN_MAX; ++f) carry[f] = read_vf(st_next, f / UB, f % UB);
         }
         if (C && !IL) {
             softmax_head(par, std::false_type{}, j);
@@ -436,13 +395,8 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
 
     // Barrier j: every wave's share of the stages up to j has landed (the copies of the stages after
     // it, at most AHEAD - 1 of them, may still be in flight) and nobody reads stage j-2 any more, so
-    // that slot takes the copies of stage j + AHEAD.  Returns that stage if it exists (else -3);
-    // with `now` the copies are issued here, otherwise the following pass issues them.
-#ifdef ATTN8_TIMING
-    unsigned long long dbg_acc[DBG8_SLOTS] = {};
-#endif
-    auto step = [&](int j, bool now) __attribute__((always_inline)) -> int {
-        TSTAMP8(t0);
+    // that slot takes the copies of stage j + AHEAD.
+    auto step = [&](int j) __attribute__((always_inline)) {
         const int n_out = min(j + AHEAD - 1, last_stage) - j;           // stages that may stay in flight
         if (n_out >= AHEAD - 1) wait_vmcnt<(AHEAD - 1) * PPW>();
         else if (n_out == 4 && AHEAD > 5) wait_vmcnt<4 * PPW>();
@@ -450,16 +404,11 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         else if (n_out == 2 && AHEAD > 3) wait_vmcnt<2 * PPW>();
         else if (n_out == 1 && AHEAD > 2) wait_vmcnt<1 * PPW>();
         else wait_vmcnt<0>();
-        TSTAMP8(t1);
         __builtin_amdgcn_s_barrier();
-        TSTAMP8(t2);
-        const int s = j + AHEAD <= last_stage ? j + AHEAD : -3;
-        if ((now || !ATTN8_SPREAD_COPIES) && s >= -2) {
-            if (stage_inside(s)) { issue_inside(s, 0); if (PPW > 1) issue_inside(s, 1); }
-            else issue_stage(s);
+        const int s = j + AHEAD;
+        if (s <= last_stage) {
+            if (stage_inside(s)) issue_inside(s); else issue_stage(s);
         }
-        TACC8(0, t0, t1); TACC8(1, t1, t2);
-        return s;
     };
     auto stage_ptr = [&](int s) __attribute__((always_inline)) -> const char* { return smem + ((s + 2 * STAGES) % STAGES) * STAGE_BYTES; };
 
@@ -490,43 +439,43 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     //   j <= nt_w - 2   MFMAs of U_{j-1} and T_{j+1}, softmax C_j in between (no tile before the last needs a mask)
     //   j == nt_w - 1   U_{j-1}, then C_j with the mask (diagonal or ragged end), then U_j (stage j is visible)
     //   j >= nt_w       nothing: the wave only keeps copying its share for the others
-    pass(NO, Y, NO, NO, NO, P1, stage_ptr(-2), nullptr, 0, -3);         // T_0 into the scores of parity 0
+    pass(NO, Y, NO, P1, stage_ptr(-2), 0);                              // T_0 into the scores of parity 0
     int j = 0;
     if (nt_w >= 2) {
-        int is = step(0, false);
-        pass(NO, Y, Y, NO, Y, P0, stage_ptr(-1), stage_ptr(0), 0, is);  // T_1 and C_0
+        step(0);
+        pass(NO, Y, Y, P0, stage_ptr(-1), 0);                           // T_1 and C_0
         j = 1;
         if (j + 1 <= nt_w - 2) {
             do {                                // bottom-tested: the accumulators are updated in place
-                is = step(j, false);
-                pass(Y, Y, Y, Y, Y, P1, stage_ptr(j - 1), stage_ptr(j), j, is);
-                is = step(j + 1, false);
-                pass(Y, Y, Y, Y, Y, P0, stage_ptr(j), stage_ptr(j + 1), j + 1, is);
+                step(j);
+                pass(Y, Y, Y, P1, stage_ptr(j - 1), j);
+                step(j + 1);
+                pass(Y, Y, Y, P0, stage_ptr(j), j + 1);
                 j += 2;
             } while (j + 1 <= nt_w - 2);
         }
         if (j <= nt_w - 2) {
-            is = step(j, false);
-            pass(Y, Y, Y, Y, Y, P1, stage_ptr(j - 1), stage_ptr(j), j, is);
+            step(j);
+            pass(Y, Y, Y, P1, stage_ptr(j - 1), j);
             ++j;
         }
     }
     // j == nt_w - 1: the last tile this wave computes on
     auto tail = [&](auto par, auto parx) __attribute__((always_inline)) {
-        step(j, true);
-        if (j >= 1) pass(Y, NO, NO, Y, NO, par, stage_ptr(j - 1), nullptr, j, -3);     // U_{j-1}
+        step(j);
+        if (j >= 1) pass(Y, NO, NO, par, stage_ptr(j - 1), j);          // U_{j-1}
         softmax_head(par, Y, j);
-        __builtin_amdgcn_sched_barrier(0);      // (slice by slice: scheduled as one block this part spills registers)
+        __builtin_amdgcn_sched_barrier(0);      // (slice by slice: scheduled as one block this part spills more registers)
 #pragma unroll
         for (int s = 0; s < KB * 4; ++s) {
             softmax_group(par, s);
             __builtin_amdgcn_sched_barrier(0);
         }
         softmax_rescale();
-        pass(Y, NO, NO, NO, NO, parx, stage_ptr(j), nullptr, j + 1, -3);               // U_j
+        pass(Y, NO, NO, parx, stage_ptr(j), j + 1);                     // U_j
     };
     if (j & 1) tail(P1, P0); else tail(P0, P1);
-    for (++j; j < nt; ++j) step(j, true);                               // idle tail of a causal wave
+    for (++j; j < nt; ++j) step(j);                               // idle tail of a causal wave
     wait_vmcnt<0>();
 
     // ---- epilogue: normalise, write O (16-bit) and LSE (natural log)
@@ -553,7 +502,6 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
 #ifdef ATTN8_TIMING
     if (blockIdx.x < DBG8_WGS && lane == 0) {
         unsigned long long* d = attn8_dbg + (blockIdx.x * 8 + wave) * DBG8_SLOTS;
-        d[0] = dbg_acc[0]; d[1] = dbg_acc[1];                      // copy wait, barrier wait
         d[5] = nt;
         d[6] = __builtin_amdgcn_s_memrealtime() - rt0;   // 100 MHz ticks
         d[7] = __builtin_readcyclecounter() - ct0;

@@ -20,8 +20,6 @@ What the axes stand for on gfx950:
              ATTN8_INTERLEAVE   softmax of tile j issued in slices between the MFMAs of U_{j-1} and T_{j+1} (1: the
                                 in-wave software pipeline of the paper's Algorithm 1) or after them as one block (0)
              ATTN8_STAGES       depth of the LDS ring (the paper's D): copies run STAGES - 2 tiles ahead
-  attn_fp8_copy ATTN8_POSTFETCH  first LDS fragments of the next tile requested before (1) or after (0) the barrier
-             ATTN8_SPREAD_COPIES copies issued between the MFMAs of a pass (1) or right after the barrier (0)
   gemm       GEMM_STAGES        depth of the LDS ring (the paper's D): 4 or 5
              GEMM_COMPUTE_WAVES waves per workgroup: 8 x (128 x 64) or 4 x (128 x 128)
              GEMM_TAIL_READS    LDS requests allowed in flight across the tile boundary
@@ -42,10 +40,9 @@ GRIDS = {
     "attn": {"ATTN_FWIN": [1, 2, 4, 8], "ATTN_COPY_GROUP": [0, 2, 1], "ATTN_SUMCHAINS": [2, 4]},
     "attn_causal": {"ATTN_PERSISTENT": [0, 1], "ATTN_FWIN": [2, 4]},
     "attn_fp8": {"ATTN8_FWIN": [1, 2, 3], "ATTN8_INTERLEAVE": [1, 0], "ATTN8_STAGES": [4, 8]},
-    "attn_fp8_copy": {"ATTN8_POSTFETCH": [0, 1], "ATTN8_SPREAD_COPIES": [0, 1]},
     "gemm": {"GEMM_STAGES": [4, 5], "GEMM_COMPUTE_WAVES": [8, 4], "GEMM_TAIL_READS": [0, 3]},
 }
-DEFAULTS = {"ATTN8_FWIN": 2, "ATTN8_INTERLEAVE": 1, "ATTN8_STAGES": 4, "ATTN8_POSTFETCH": 0, "ATTN8_SPREAD_COPIES": 0, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
+DEFAULTS = {"ATTN8_FWIN": 2, "ATTN8_INTERLEAVE": 1, "ATTN8_STAGES": 4, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
             "GEMM_STAGES": 4, "GEMM_COMPUTE_WAVES": 8, "GEMM_TAIL_READS": 3}
 
 
@@ -113,7 +110,7 @@ def cmd_run(args) -> int:
             flops, what = 2.0 * M * N * K, "gemm_nt M=N=8192 K=%d fp16" % K
             call = lambda lib: lib.gemm_nt(a.data_ptr(), b.data_ptr(), out.data_ptr(), M, N, K, stream, 0)
             view = lambda: out.view(torch.float16)[::509, ::263].float().cpu().numpy()
-        elif op in ("attn_fp8", "attn_fp8_copy"):
+        elif op == "attn_fp8":
             w = I.FP8_WORKLOADS[args.fp8_workload]
             q, k, v = (torch.from_numpy(x).cuda() for x in I.make_workload(w))
             out = torch.empty((w.B, w.H, w.N, w.d), dtype=torch.int16, device="cuda")
