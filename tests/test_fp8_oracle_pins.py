@@ -59,6 +59,23 @@ def test_rounding_to_e4m3_matches_torch_and_saturates():
     assert I.f32_to_e4m3_bits(np.float32([464.0, 1e9, -1e9])).tolist() == [0x7E, 0x7E, 0xFE]
 
 
+def test_two_key_logistic_closed_form_in_e4m3(oracle):
+    """The hand-worked case of ``golden/two_key_logistic.txt`` (q = [1, 1], k = [0, 1], v = [0, 1], d = 1,
+    scale 1: O = logistic(1), LSE = softplus(1)); every input is exactly representable in E4M3."""
+    vals = dict(l.split() for l in open(os.path.join(GOLDEN, "two_key_logistic.txt")) if l.strip() and not l.startswith("#"))
+    one, zero = 0x38, 0x00
+    q = np.array([one, one], dtype=np.uint8).reshape(1, 1, 2, 1)
+    k = np.array([zero, one], dtype=np.uint8).reshape(1, 1, 2, 1)
+    v = np.array([zero, one], dtype=np.uint8).reshape(1, 1, 2, 1)
+    o, lse = oracle.attn_ref(q, k, v, E4M3, 1.0, False)
+    assert np.max(np.abs(o - float(vals["O"]))) < 1e-15
+    assert np.max(np.abs(lse - float(vals["LSE"]))) < 1e-15
+    # causal: row 0 sees only key 0 (O = v_0 = 0, LSE = s_00 = 0), row 1 is the case above
+    o, lse = oracle.attn_ref(q, k, v, E4M3, 1.0, True)
+    assert o[0, 0, 0, 0] == 0.0 and lse[0, 0, 0] == 0.0
+    assert abs(o[0, 0, 1, 0] - float(vals["O"])) < 1e-15 and abs(lse[0, 0, 1] - float(vals["LSE"])) < 1e-15
+
+
 @pytest.mark.parametrize("causal", [False, True])
 def test_zero_q_gives_mean_of_visible_v(oracle, causal):
     B, H, N, d = 2, 2, 29, 8

@@ -81,6 +81,53 @@ def test_fp8_workloads_sampled_rows(G, oracle, name):
         G.check(og, lg, o_ref, l_ref, name + " (16-bit tolerances)")
 
 
+# ------------------------------------------------------------ properties that hold at any size
+def test_f4_properties(G, oracle):
+    """Full sequence length, two heads: O stays inside the convex hull of the V rows (it is normalised by
+    the sum of the rounded probabilities), and splitting the keys into two halves and merging the two
+    (O, LSE) pairs by their LSE reproduces the one-shot result -- the identity a key-sharded run relies on."""
+    w = I.FP8_WORKLOADS["f4"]
+    N, d = w.N, w.d
+    q, k, v = I.make_qkv(1, 2, N, d, E4M3, w.seed)
+    o, l = G.run_gpu_fp8(q, k, v, I.FP16, w.scale, False)
+    vf = G.e4m3_to_f64(v)
+    assert np.all(o.max(axis=2) <= vf.max(axis=2) + 1e-3) and np.all(o.min(axis=2) >= vf.min(axis=2) - 1e-3)
+    h = N // 2
+    # queries 0 .. h-1 against each half of the keys (the kernel takes N queries = N keys, so run the
+    # halves as sequences of their own with the first h queries)
+    o1, l1 = G.run_gpu_fp8(np.ascontiguousarray(q[:, :, :h]), np.ascontiguousarray(k[:, :, :h]), np.ascontiguousarray(v[:, :, :h]), I.FP16, w.scale, False)
+    o2, l2 = G.run_gpu_fp8(np.ascontiguousarray(q[:, :, :h]), np.ascontiguousarray(k[:, :, h:]), np.ascontiguousarray(v[:, :, h:]), I.FP16, w.scale, False)
+    lm = np.logaddexp(l1, l2)
+    om = np.exp(l1 - lm)[..., None] * o1 + np.exp(l2 - lm)[..., None] * o2
+    # both sides carry independent E4M3 rounding of ~8000 probabilities per row: a few 1e-3
+    assert np.abs(om - o[:, :, :h]).max() < 1e-2 and np.abs(om - o[:, :, :h]).mean() < 1e-3
+    assert np.abs(lm - l[:, :, :h]).max() < 5e-3
+    # ... and against the oracle on a few of those rows
+    rows = [(0, 0, 0), (0, 1, h - 1), (0, 0, 1234), (0, 1, 4321)]
+    o_ref, l_ref = oracle.attn_ref_rows(q, k, v, E4M3, rows, w.scale, False)
+    idx = np.asarray(rows)
+    assert np.abs(om[idx[:, 0], idx[:, 1], idx[:, 2]] - o_ref).max() < 1e-2
+    assert np.abs(lm[idx[:, 0], idx[:, 1], idx[:, 2]] - l_ref).max() < 5e-3
+
+
+def test_single_head_and_other_stream(G, oracle):
+    """B*H = 1 (four workgroups), launched on a stream of its own."""
+    import torch
+    from paper_2510_14719_amd import binding
+    B, H, N, d = 1, 1, 1000, 128
+    q, k, v = I.make_qkv(B, H, N, d, E4M3, 199)
+    o_ref, l_ref, p = oracle.attn_ref(q, k, v, E4M3, 0.1, True, return_p=True)
+    dq, dk, dv = (torch.from_numpy(x).cuda() for x in (q, k, v))
+    o = torch.empty((B, H, N, d), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    binding.attn_fwd_fp8(dq, dk, dv, o, lse, B, H, N, d, 0.1, True, stream=st)
+    st.synchronize()
+    bo, bl = G.fp8_bounds(p, G.e4m3_to_f64(v), o_ref, I.BF16)
+    G.check_fp8(o.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, l_ref, bo, bl, "single head, own stream")
+
+
 # ------------------------------------------------------------ exact and degenerate cases
 @pytest.mark.parametrize("causal", [False, True])
 def test_zero_q_gives_running_mean(G, oracle, causal):
