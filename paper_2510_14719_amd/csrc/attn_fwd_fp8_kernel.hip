@@ -76,6 +76,12 @@ constexpr float RESCALE_LOG2_FP8 = 8.0f;
 #define ATTN8_INTERLEAVE 1
 #endif
 
+// 1: in the steady state the copies of a stage are issued inside the pass, one piece behind each of a few
+// MFMAs; 0: all of them right after the barrier.
+#ifndef ATTN8_COPIES_IN_PASS
+#define ATTN8_COPIES_IN_PASS 1
+#endif
+
 #ifdef ATTN8_TIMING
 // Profiling builds only: cycle and wall-clock totals of the main loop of the first workgroups.
 constexpr int DBG8_WGS = 1024, DBG8_SLOTS = 8;
@@ -334,8 +340,12 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     // first MFMA, then one slice of scores after each of the others.  The scheduling barriers keep
     // that order.  (Measured: the row maximum before the first MFMA, the ones block first, or the
     // maximum in four independent chains each change the time by 1-3 % the wrong way.)
-    auto pass = [&](auto do_u, auto do_t, auto do_c, auto par, const char* st, int j) __attribute__((always_inline)) {
+    // `copies`: the pass also issues the copies of stage j + AHEAD (known to lie wholly inside the
+    // sequence), one piece after each of a few MFMAs: the wave is held while a copy instruction hands
+    // its addresses to the memory pipeline, and behind an MFMA of its own that time costs nothing.
+    auto pass = [&](auto do_u, auto do_t, auto do_c, auto copies, auto par, const char* st, int j) __attribute__((always_inline)) {
         constexpr int P = decltype(par)::value;
+        constexpr bool COPIES = decltype(copies)::value;
         constexpr bool C = decltype(do_c)::value;
         constexpr int UB = DB + 1;                                      // per 64 keys: DB feature blocks, then the ones block
         constexpr int NU = decltype(do_u)::value ? KC * UB : 0;
@@ -374,6 +384,17 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
             if (f + FWIN < NF) fetch(f + FWIN);
             run_mfma(f);
             __builtin_amdgcn_sched_barrier(0);
+            if (COPIES) {
+                // pieces after MFMAs 1, 3, 5, ... (the first MFMA is followed by the row maximum)
+#pragma unroll
+                for (int i = 0; i < PPW; ++i)
+                    if (f == 1 + 2 * i || (1 + 2 * i >= NF && f == NF - 1 && i >= (NF - 1) / 2)) {
+                        const int s = j + AHEAD;
+                        dma16(piece_src[i] + (size_t)s * TILE_BYTES, piece_lane_off[i],
+                              lds_base + ((s + 2 * STAGES) % STAGES) * STAGE_BYTES + piece_dst[i]);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if (IL) {
                 if (f == 0) {
                     softmax_head(par, std::false_type{}, j);
@@ -396,7 +417,7 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     // Barrier j: every wave's share of the stages up to j has landed (the copies of the stages after
     // it, at most AHEAD - 1 of them, may still be in flight) and nobody reads stage j-2 any more, so
     // that slot takes the copies of stage j + AHEAD.
-    auto step = [&](int j) __attribute__((always_inline)) {
+    auto step = [&](int j, bool with_copies = true) __attribute__((always_inline)) {
         const int n_out = min(j + AHEAD - 1, last_stage) - j;           // stages that may stay in flight
         if (n_out >= AHEAD - 1) wait_vmcnt<(AHEAD - 1) * PPW>();
         else if (n_out == 4 && AHEAD > 5) wait_vmcnt<4 * PPW>();
@@ -406,7 +427,7 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
         const int s = j + AHEAD;
-        if (s <= last_stage) {
+        if (with_copies && s <= last_stage) {
             if (stage_inside(s)) issue_inside(s); else issue_stage(s);
         }
     };
@@ -439,31 +460,42 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     //   j <= nt_w - 2   MFMAs of U_{j-1} and T_{j+1}, softmax C_j in between (no tile before the last needs a mask)
     //   j == nt_w - 1   U_{j-1}, then C_j with the mask (diagonal or ragged end), then U_j (stage j is visible)
     //   j >= nt_w       nothing: the wave only keeps copying its share for the others
-    pass(NO, Y, NO, P1, stage_ptr(-2), 0);                              // T_0 into the scores of parity 0
+    pass(NO, Y, NO, NO, P1, stage_ptr(-2), 0);                          // T_0 into the scores of parity 0
     int j = 0;
     if (nt_w >= 2) {
         step(0);
-        pass(NO, Y, Y, P0, stage_ptr(-1), 0);                           // T_1 and C_0
+        pass(NO, Y, Y, NO, P0, stage_ptr(-1), 0);                       // T_1 and C_0
         j = 1;
-        if (j + 1 <= nt_w - 2) {
+        // first the iterations whose copies (stage j + AHEAD) lie wholly inside the sequence: the pass issues them
+        const int j_in = min(nt_w - 2, N / BN - AHEAD - 3);
+        if (ATTN8_COPIES_IN_PASS && j + 1 <= j_in) {
             do {                                // bottom-tested: the accumulators are updated in place
+                step(j, false);
+                pass(Y, Y, Y, Y, P1, stage_ptr(j - 1), j);
+                step(j + 1, false);
+                pass(Y, Y, Y, Y, P0, stage_ptr(j), j + 1);
+                j += 2;
+            } while (j + 1 <= j_in);
+        }
+        if (j + 1 <= nt_w - 2) {
+            do {
                 step(j);
-                pass(Y, Y, Y, P1, stage_ptr(j - 1), j);
+                pass(Y, Y, Y, NO, P1, stage_ptr(j - 1), j);
                 step(j + 1);
-                pass(Y, Y, Y, P0, stage_ptr(j), j + 1);
+                pass(Y, Y, Y, NO, P0, stage_ptr(j), j + 1);
                 j += 2;
             } while (j + 1 <= nt_w - 2);
         }
         if (j <= nt_w - 2) {
             step(j);
-            pass(Y, Y, Y, P1, stage_ptr(j - 1), j);
+            pass(Y, Y, Y, NO, P1, stage_ptr(j - 1), j);
             ++j;
         }
     }
     // j == nt_w - 1: the last tile this wave computes on
     auto tail = [&](auto par, auto parx) __attribute__((always_inline)) {
         step(j);
-        if (j >= 1) pass(Y, NO, NO, par, stage_ptr(j - 1), j);          // U_{j-1}
+        if (j >= 1) pass(Y, NO, NO, NO, par, stage_ptr(j - 1), j);      // U_{j-1}
         softmax_head(par, Y, j);
         __builtin_amdgcn_sched_barrier(0);      // (slice by slice: scheduled as one block this part spills more registers)
 #pragma unroll
@@ -472,7 +504,7 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
             __builtin_amdgcn_sched_barrier(0);
         }
         softmax_rescale();
-        pass(Y, NO, NO, parx, stage_ptr(j), j + 1);                     // U_j
+        pass(Y, NO, NO, NO, parx, stage_ptr(j), j + 1);                 // U_j
     };
     if (j & 1) tail(P1, P0); else tail(P0, P1);
     for (++j; j < nt; ++j) step(j);                               // idle tail of a causal wave

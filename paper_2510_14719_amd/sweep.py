@@ -20,6 +20,7 @@ What the axes stand for on gfx950:
              ATTN8_INTERLEAVE   softmax of tile j issued in slices between the MFMAs of U_{j-1} and T_{j+1} (1: the
                                 in-wave software pipeline of the paper's Algorithm 1) or after them as one block (0)
              ATTN8_STAGES       depth of the LDS ring (the paper's D): copies run STAGES - 2 tiles ahead
+             ATTN8_COPIES_IN_PASS copies issued one by one behind MFMAs of the pass (1) or all right after the barrier (0)
   gemm       GEMM_STAGES        depth of the LDS ring (the paper's D): 4 or 5
              GEMM_COMPUTE_WAVES waves per workgroup: 8 x (128 x 64) or 4 x (128 x 128)
              GEMM_TAIL_READS    LDS requests allowed in flight across the tile boundary
@@ -39,10 +40,10 @@ VARIANT_DIR = os.path.join(HERE, "sweep_variants")
 GRIDS = {
     "attn": {"ATTN_FWIN": [1, 2, 4, 8], "ATTN_COPY_GROUP": [0, 2, 1], "ATTN_SUMCHAINS": [2, 4]},
     "attn_causal": {"ATTN_PERSISTENT": [0, 1], "ATTN_FWIN": [2, 4]},
-    "attn_fp8": {"ATTN8_FWIN": [1, 2, 3], "ATTN8_INTERLEAVE": [1, 0], "ATTN8_STAGES": [4, 8]},
+    "attn_fp8": {"ATTN8_FWIN": [1, 2, 3], "ATTN8_INTERLEAVE": [1, 0], "ATTN8_STAGES": [4, 8], "ATTN8_COPIES_IN_PASS": [1, 0]},
     "gemm": {"GEMM_STAGES": [4, 5], "GEMM_COMPUTE_WAVES": [8, 4], "GEMM_TAIL_READS": [0, 3]},
 }
-DEFAULTS = {"ATTN8_FWIN": 2, "ATTN8_INTERLEAVE": 1, "ATTN8_STAGES": 4, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
+DEFAULTS = {"ATTN8_FWIN": 2, "ATTN8_INTERLEAVE": 1, "ATTN8_STAGES": 4, "ATTN8_COPIES_IN_PASS": 1, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
             "GEMM_STAGES": 4, "GEMM_COMPUTE_WAVES": 8, "GEMM_TAIL_READS": 3}
 
 
