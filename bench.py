@@ -32,7 +32,7 @@ DTYPE_NAME = {0: "fp16", 1: "bf16", 2: "fp8-e4m3"}
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each scaled by
 # what the counter reads for a 1 GiB copy); a profile's figure, not measured by this script.
 MEASURED_TRAFFIC = {"c4": ((163994.6 * 2.000 + 67133.9 * 1.000) * 1024.0, "profiles/attn_fwd_c4_fp16_noncausal.md"),
-                    "f4": ((91686.3 * 2.000 + 103424.0 * 1.000) * 1024.0, "profiles/attn_fwd_fp8_f4_e4m3_noncausal.md")}
+                    "f4": ((89711.5 * 2.000 + 105472.0 * 1.000) * 1024.0, "profiles/attn_fwd_fp8_f4_e4m3_noncausal.md")}
 
 
 def describe(w) -> str:
