@@ -23,6 +23,7 @@ _LIB = os.path.join(_HERE, "libgemm_ref.so")
 
 FP16 = 0
 BF16 = 1
+E4M3 = 2     # OCP 8-bit float, stored as uint8
 
 _lib = None
 
@@ -42,7 +43,8 @@ def _load():
     if _lib is None:
         build()
         lib = ctypes.CDLL(_LIB)
-        u16p, f64p, i32p = (ctypes.POINTER(t) for t in (ctypes.c_uint16, ctypes.c_double, ctypes.c_int))
+        f64p, i32p = (ctypes.POINTER(t) for t in (ctypes.c_double, ctypes.c_int))
+        u16p = ctypes.c_void_p          # raw storage patterns: uint16 (fp16, bf16) or uint8 (E4M3)
         ci = ctypes.c_int
         lib.gemm_ref_nt_f64.restype = ci
         lib.gemm_ref_nt_f64.argtypes = [u16p, u16p, ci, f64p, ci, ci, ci, ci]
@@ -56,13 +58,22 @@ def _load():
     return _lib
 
 
-def _u16(a, shape):
+def _storage(dtype: int):
+    return np.uint8 if dtype == E4M3 else np.uint16
+
+
+def _bits(a, shape, dtype: int):
     a = np.ascontiguousarray(a)
-    if a.dtype != np.uint16:
-        raise TypeError("oracle inputs are raw uint16 bit patterns, got %s" % a.dtype)
+    if a.dtype != _storage(dtype):
+        raise TypeError("oracle inputs are raw %s bit patterns for dtype %d, got %s"
+                        % (np.dtype(_storage(dtype)).name, dtype, a.dtype))
     if tuple(a.shape) != tuple(shape):
         raise ValueError("expected shape %s, got %s" % (shape, a.shape))
     return a
+
+
+def _raw(a):
+    return ctypes.c_void_p(a.ctypes.data)
 
 
 def _ptr(a, ctype):
@@ -74,20 +85,20 @@ def max_threads() -> int:
 
 
 def decode(bits, dtype: int) -> np.ndarray:
-    """Exact fp16/bf16 bit pattern -> float64, by the oracle's own decoder."""
-    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    """Exact fp16/bf16/E4M3 bit pattern -> float64, by the oracle's own decoder."""
+    bits = np.ascontiguousarray(bits, dtype=_storage(dtype))
     out = np.empty(bits.shape, dtype=np.float64)
-    _load().gemm_ref_decode(_ptr(bits, ctypes.c_uint16), _ptr(out, ctypes.c_double), bits.size, dtype)
+    _load().gemm_ref_decode(_raw(bits), _ptr(out, ctypes.c_double), bits.size, dtype)
     return out
 
 
 def gemm_nt(a, b, dtype: int, nthreads: int = 0) -> np.ndarray:
-    """``C = A B^T`` in fp64 for ``a`` [M,K] and ``b`` [N,K] uint16 bit patterns; returns [M,N] float64."""
+    """``C = A B^T`` in fp64 for ``a`` [M,K] and ``b`` [N,K] bit patterns (uint16, or uint8 for E4M3); returns [M,N] float64."""
     M, K = a.shape
     N = b.shape[0]
-    a = _u16(a, (M, K)); b = _u16(b, (N, K))
+    a = _bits(a, (M, K), dtype); b = _bits(b, (N, K), dtype)
     c = np.empty((M, N), dtype=np.float64)
-    rc = _load().gemm_ref_nt_f64(_ptr(a, ctypes.c_uint16), _ptr(b, ctypes.c_uint16), dtype, _ptr(c, ctypes.c_double),
+    rc = _load().gemm_ref_nt_f64(_raw(a), _raw(b), dtype, _ptr(c, ctypes.c_double),
                                  M, N, K, int(nthreads))
     if rc != 0:
         raise RuntimeError("gemm_ref_nt_f64 failed with code %d" % rc)
@@ -98,10 +109,10 @@ def gemm_nt_samples(a, b, dtype: int, idx) -> np.ndarray:
     """The same definition for sampled entries ``idx = [(m, n), ...]``; returns [len(idx)] float64."""
     M, K = a.shape
     N = b.shape[0]
-    a = _u16(a, (M, K)); b = _u16(b, (N, K))
+    a = _bits(a, (M, K), dtype); b = _bits(b, (N, K), dtype)
     idx = np.ascontiguousarray(np.asarray(idx, dtype=np.int32).reshape(-1, 2))
     out = np.empty((idx.shape[0],), dtype=np.float64)
-    rc = _load().gemm_ref_nt_samples_f64(_ptr(a, ctypes.c_uint16), _ptr(b, ctypes.c_uint16), dtype,
+    rc = _load().gemm_ref_nt_samples_f64(_raw(a), _raw(b), dtype,
                                          _ptr(idx, ctypes.c_int), idx.shape[0], _ptr(out, ctypes.c_double), M, N, K)
     if rc != 0:
         raise RuntimeError("gemm_ref_nt_samples_f64 failed with code %d" % rc)

@@ -151,7 +151,7 @@ GEMM_K_SWEEP = (256, 512, 1024, 2048, 4096, 8192, 16384)
 
 
 def make_ab(M: int, N: int, K: int, dtype: int, seed: int):
-    """A ``[M,K]`` and B ``[N,K]`` (both K-contiguous) as uint16 bit patterns; seeds ``seed, seed+1``."""
+    """A ``[M,K]`` and B ``[N,K]`` (both K-contiguous) as bit patterns (uint16, or uint8 for E4M3); seeds ``seed, seed+1``."""
     return normal_bits((M, K), dtype, seed), normal_bits((N, K), dtype, seed + 1)
 
 

@@ -38,7 +38,7 @@ def read_golden():
     return {k: np.array(v) for k, v in mats.items()}
 
 
-@pytest.mark.parametrize("dtype", [I.FP16, I.BF16])
+@pytest.mark.parametrize("dtype", [I.FP16, I.BF16, I.E4M3])
 def test_hand_worked_example(G, dtype):
     g = read_golden()
     c = G.gemm_nt(bits_of(g["A"], dtype), bits_of(g["B"], dtype), dtype)
@@ -59,7 +59,23 @@ def test_decoders_on_known_patterns(G):
     assert np.array_equal(G.decode(allbits, I.FP16), allbits.view(np.float16).astype(np.float64))
 
 
-@pytest.mark.parametrize("dtype", [I.FP16, I.BF16])
+def test_e4m3_decoder_against_torch_and_the_format_table(G):
+    import torch
+    allbits = np.arange(256, dtype=np.uint8)
+    got = G.decode(allbits, I.E4M3)
+    want = torch.from_numpy(allbits).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    nan = np.isnan(want)
+    assert nan.sum() == 2 and np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan]) and np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+    table = os.path.join(os.path.dirname(GOLDEN), "e4m3_values.txt")
+    for line in open(table):
+        if line.strip() and not line.startswith("#"):
+            pat, val = line.split()
+            g = G.decode(np.array([int(pat, 16)], dtype=np.uint8), I.E4M3)[0]
+            assert (np.isnan(g) and val == "nan") or g == float(val)
+
+
+@pytest.mark.parametrize("dtype", [I.FP16, I.BF16, I.E4M3])
 def test_exact_rational_arithmetic_on_tiny_inputs(G, dtype):
     M, N, K = 3, 5, 7                       # all different: a transposed operand cannot go unnoticed
     a, b = I.make_ab(M, N, K, dtype, seed=11)
@@ -92,7 +108,7 @@ def test_rank_one(G):
     assert np.array_equal(G.gemm_nt(u, v, I.FP16), want)
 
 
-@pytest.mark.parametrize("dtype", [I.FP16, I.BF16])
+@pytest.mark.parametrize("dtype", [I.FP16, I.BF16, I.E4M3])
 def test_transpose_split_k_and_scaling_identities(G, dtype):
     M, N, K = 13, 21, 96
     a, b = I.make_ab(M, N, K, dtype, seed=13)
@@ -108,12 +124,15 @@ def test_transpose_split_k_and_scaling_identities(G, dtype):
     assert np.array_equal(G.gemm_nt(a, b[7:10], dtype), c[:, 7:10])
 
 
-@pytest.mark.parametrize("dtype", [I.FP16, I.BF16])
+@pytest.mark.parametrize("dtype", [I.FP16, I.BF16, I.E4M3])
 def test_against_library_matmul_with_independent_decoder(G, dtype):
     M, N, K = 70, 45, 300
     a, b = I.make_ab(M, N, K, dtype, seed=14)
     if dtype == I.FP16:
         da, db = a.view(np.float16).astype(np.float64), b.view(np.float16).astype(np.float64)
+    elif dtype == I.E4M3:
+        import torch
+        da, db = (torch.from_numpy(x).view(torch.float8_e4m3fn).to(torch.float64).numpy() for x in (a, b))
     else:
         da = (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
         db = (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
