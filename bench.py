@@ -32,7 +32,9 @@ DTYPE_NAME = {0: "fp16", 1: "bf16", 2: "fp8-e4m3"}
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each scaled by
 # what the counter reads for a 1 GiB copy); a profile's figure, not measured by this script.
 MEASURED_TRAFFIC = {"c4": ((163994.6 * 2.000 + 67133.9 * 1.000) * 1024.0, "profiles/attn_fwd_c4_fp16_noncausal.md"),
-                    "f4": ((89711.5 * 2.000 + 105472.0 * 1.000) * 1024.0, "profiles/attn_fwd_fp8_f4_e4m3_noncausal.md")}
+                    "f4": ((89711.5 * 2.000 + 105472.0 * 1.000) * 1024.0, "profiles/attn_fwd_fp8_f4_e4m3_noncausal.md"),
+                    ("gemm", 16384): ((3267434.0 * 2.000 + 138227.0 * 1.000) * 1024.0, "profiles/gemm_nt_m8192_n8192_k16384_fp16.md"),
+                    ("gemm_fp8", 16384): ((801891.4 * 2.000 + 138042.0 * 1.000) * 1024.0, "profiles/gemm_nt_fp8_m8192_n8192_k16384_e4m3.md")}
 
 
 def describe(w) -> str:
@@ -96,7 +98,8 @@ def gemm_cpu_baseline(M, N, K, dtype, seed, rows: int = 24) -> dict:
 
 
 def main_gemm(args) -> int:
-    """`--op gemm`: the paper's matrix-multiplication workload, M = N = 8192, one K of its sweep."""
+    """`--op gemm` / `--op gemm_fp8`: the paper's matrix-multiplication workload, M = N = 8192, one K of
+    its sweep, on fp16 operands or on 8-bit-float (E4M3) operands with an fp16 result."""
     import numpy as np
     import torch
     from paper_2510_14719_amd import binding, inputs as I
@@ -105,16 +108,20 @@ def main_gemm(args) -> int:
         return 3
     binding.load_library()
     M = N = 8192
-    K, dtype, seed = args.K, I.FP16, 7000 + args.K
+    fp8 = args.op == "gemm_fp8"
+    K, dtype, seed = args.K, (I.E4M3 if fp8 else I.FP16), 7000 + args.K
     a_bits, b_bits = I.make_ab(M, N, K, dtype, seed)
-    a = torch.from_numpy(a_bits.view("int16")).cuda()
-    b = torch.from_numpy(b_bits.view("int16")).cuda()
+    a = torch.from_numpy(a_bits if fp8 else a_bits.view("int16")).cuda()
+    b = torch.from_numpy(b_bits if fp8 else b_bits.view("int16")).cuda()
     c = torch.empty((M, N), dtype=torch.int16, device="cuda")
     stream = torch.cuda.current_stream()
     flops = 2.0 * M * N * K
 
     def step():
-        binding.gemm_nt(a, b, c, M, N, K, stream=stream, dtype=dtype)
+        if fp8:
+            binding.gemm_nt_fp8(a, b, c, M, N, K, stream=stream, out_dtype=I.FP16)
+        else:
+            binding.gemm_nt(a, b, c, M, N, K, stream=stream, dtype=dtype)
 
     for _ in range(args.warmup):
         step()
@@ -134,14 +141,18 @@ def main_gemm(args) -> int:
     out = {
         "metric": "matrix product C = A B^T TFLOP/s (2*M*N*K), 1 GPU", "value": flops / (ms_per_step * 1e-3) * 1e-12,
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "gemm_nt: M=8192 N=8192 K=%d fp16" % K, "tile": binding.gemm_tile_params(),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f8e4m3" if fp8 else "f16", "data": "synthetic",
+        "config": {"workload": "gemm_nt: M=8192 N=8192 K=%d %s" % (K, "E4M3 operands, fp16 result" if fp8 else "fp16"),
+                   "tile": binding.gemm_fp8_tile_params() if fp8 else binding.gemm_tile_params(),
                    "flops_per_step": flops, "wall_s_timed_region": wall},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_TFLOPS[dtype], "traffic": None,
+                     "frac": achieved / PEAK_TFLOPS[dtype],
+                     "traffic": MEASURED_TRAFFIC[(args.op, K)][0] if (args.op, K) in MEASURED_TRAFFIC else None,
+                     "traffic_unit": "bytes of HBM traffic per launch (rocprofv3 counters, see %s)"
+                                     % MEASURED_TRAFFIC[(args.op, K)][1] if (args.op, K) in MEASURED_TRAFFIC else None,
                      "kernel_ms": {"mean": kern_ms, "median": statistics.median(per_launch), "min": min(per_launch)}},
         "context": {"paper_h100_fp16_gemm_tflops_k16384": 718.0,
-                    "paper_workload": "H100 SXM5, M=N=8192, K=16384 (Section 5.6); other hardware, not a target"},
+                    "paper_workload": "H100 SXM5, M=N=8192, K=16384, fp16 (Section 5.6); other hardware, not a target"},
     }
     if not args.no_mfma_probe:
         sus = mfma_sustained(binding, torch, dtype, stream)
@@ -155,8 +166,13 @@ def main_gemm(args) -> int:
         ref = gemm_ref.gemm_nt_samples(a_bits, b_bits, dtype, idx)
         ii = np.asarray(idx)
         got = c.view(torch.float16)[ii[:, 0], ii[:, 1]].double().cpu().numpy()
+        slack = 2e-6 * K
+        if fp8:   # the tests' tolerance: half an ulp of the result plus 2^-14 of sum_k |a_k b_k|
+            af, bf = (torch.from_numpy(np.ascontiguousarray(x[ii[:, j]])).view(torch.float8_e4m3fn).double().abs().numpy()
+                      for x, j in ((a_bits, 0), (b_bits, 1)))
+            slack = 2.0 ** -14 * (af * bf).sum(axis=1)
         out["parity_sample"] = {"entries": len(idx), "max_abs": float(np.abs(got - ref).max()),
-                                "max_rel_to_half_ulp": float((np.abs(got - ref) / (2.0 ** -11 * np.abs(ref) + 2e-6 * K)).max())}
+                                "max_rel_to_tolerance": float((np.abs(got - ref) / (2.0 ** -11 * np.abs(ref) + slack)).max())}
         out["cpu_baseline"] = gemm_cpu_baseline(M, N, K, dtype, seed)
     print(json.dumps(out), flush=True)
     return 0
@@ -164,8 +180,9 @@ def main_gemm(args) -> int:
 
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--op", default="attn", choices=["attn", "gemm"],
-                    help="attn: the headline attention workloads (default); gemm: the paper's M=N=8192 matrix product")
+    ap.add_argument("--op", default="attn", choices=["attn", "gemm", "gemm_fp8"],
+                    help="attn: the headline attention workloads (default); gemm: the paper's M=N=8192 matrix product "
+                         "in fp16; gemm_fp8: the same on E4M3 operands")
     ap.add_argument("--K", type=int, default=16384, help="inner dimension of --op gemm (the paper sweeps 256 ... 16384)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
@@ -186,7 +203,7 @@ def main() -> int:
               "communication and no multi-GPU figure is produced (asked for --gpus %d)" % args.gpus, file=sys.stderr)
         return 2
 
-    if args.op == "gemm":
+    if args.op in ("gemm", "gemm_fp8"):
         return main_gemm(args)
 
     import torch
@@ -288,7 +305,7 @@ def main() -> int:
     if fp8:
         out["context"] = {"paper": "the paper plots FP8 attention (Section 5.4) without printing a number for it",
                           "p_precision": "probabilities rounded to E4M3 before P V; O in fp16"}
-    if not args.no_mfma_probe and not fp8:
+    if not args.no_mfma_probe:
         # outside the timed region: the measured MFMA-only rates next to the datasheet peak
         sus = mfma_sustained(binding, torch, w.dtype, stream)
         sus["unit"] = "TFLOP/s"

@@ -137,11 +137,18 @@ int attn_fwd_tile_schedule(int total, int grid, int block, int round);
  *   sink   DEVICE pointer, written: attn_fwd_mfma_probe_sink_floats(workgroups) floats, 4-byte aligned.
  * Returns ATTN_FWD_OK, ATTN_FWD_ERR_NULL, ATTN_FWD_ERR_SHAPE (workgroups outside 1..65536, iters outside
  * 1..2^24, unknown dtype), ATTN_FWD_ERR_ALIGN or ATTN_FWD_ERR_LAUNCH; validation precedes any HIP call.
+ *
+ * dtype may also be ATTN_FWD_PROBE_E4M3: then the stream consists of 32x32x64 MFMAs on 8-bit-float
+ * (E4M3) operands, four times the work per instruction (the roofline of attn_fwd_fp8 and gemm_nt_fp8).
  */
+enum { ATTN_FWD_PROBE_E4M3 = 2 };
 int attn_fwd_mfma_probe(float *sink, int workgroups, int iters, int random_operands, int dtype, void *stream);
 
-/* Floating-point operations one such launch executes (0.0 for non-positive arguments). */
+/* Floating-point operations one such launch executes with 16-bit operands (0.0 for non-positive arguments). */
 double attn_fwd_mfma_probe_flops(int workgroups, int iters);
+
+/* The same for any element type of the probe (0.0 for an unknown dtype). */
+double attn_fwd_mfma_probe_flops_of(int workgroups, int iters, int dtype);
 
 /* Number of floats the launch writes to `sink` (-1 for workgroups outside 1..65536). */
 int attn_fwd_mfma_probe_sink_floats(int workgroups);

@@ -53,6 +53,27 @@ int gemm_nt_bf16(const void *a, const void *b, void *c, int M, int N, int K, voi
 /* Host-only argument check: what gemm_nt would return before launching. */
 int gemm_nt_check_args(const void *a, const void *b, const void *c, int M, int N, int K, int dtype);
 
+/*
+ * The product of 8-bit-float operands: the paper measures its matrix multiplication in FP16 and in FP8
+ * (Section 5.2, M = N = 8192, K from 256 to 16384).
+ *
+ *   a, b       DEVICE pointers, read only, [M][K] and [N][K] row-major bytes in the OCP E4M3 format
+ *              (1 sign, 4 exponent bits with bias 7, 3 fraction bits; no infinities, S.1111.111 is NaN).
+ *   c          DEVICE pointer, written, [M][N] row-major 16-bit elements of type out_dtype.  Every element
+ *              is overwritten.  Must not overlap a or b.
+ *   K          >= 64 and a multiple of 64 (the K tile of this kernel).
+ *   out_dtype  GEMM_NT_FP16 or GEMM_NT_BF16.
+ *
+ * The products of two E4M3 values are exact; they are summed in fp32 on the matrix cores (64 products per
+ * instruction, added to the running fp32 sum) and the result is rounded to nearest even once.  Alignment,
+ * ownership, stream semantics, thread safety and error codes are those of gemm_nt; GEMM_NT_ERR_SHAPE also
+ * covers K < 64 or K not a multiple of 64, GEMM_NT_ERR_OVERFLOW M*K or N*K >= 2^31 bytes.
+ */
+int gemm_nt_fp8(const void *a, const void *b, void *c, int M, int N, int K, void *stream, int out_dtype);
+
+/* Host-only argument check: what gemm_nt_fp8 would return before launching. */
+int gemm_nt_fp8_check_args(const void *a, const void *b, const void *c, int M, int N, int K, int out_dtype);
+
 /* Static, NUL-terminated description of a return code.  Never NULL. */
 const char *gemm_nt_strerror(int code);
 
@@ -61,6 +82,9 @@ const char *gemm_nt_strerror(int code);
  * 2 K tile, 3 LDS stages, 4 threads per workgroup.  Returns -1 for an unknown `which`.
  */
 int gemm_nt_tile_param(int which);
+
+/* The same for the kernel behind gemm_nt_fp8. */
+int gemm_nt_fp8_tile_param(int which);
 
 #ifdef __cplusplus
 }

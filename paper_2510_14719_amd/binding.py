@@ -67,6 +67,8 @@ def load_library() -> ctypes.CDLL:
         lib.attn_fwd_mfma_probe.argtypes = [vp, ci, ci, ci, ci, vp]
         lib.attn_fwd_mfma_probe_flops.restype = ctypes.c_double
         lib.attn_fwd_mfma_probe_flops.argtypes = [ci, ci]
+        lib.attn_fwd_mfma_probe_flops_of.restype = ctypes.c_double
+        lib.attn_fwd_mfma_probe_flops_of.argtypes = [ci, ci, ci]
         lib.attn_fwd_mfma_probe_sink_floats.restype = ci
         lib.attn_fwd_mfma_probe_sink_floats.argtypes = [ci]
         lib.gemm_nt.restype = ci
@@ -81,6 +83,12 @@ def load_library() -> ctypes.CDLL:
         lib.gemm_nt_strerror.argtypes = [ci]
         lib.gemm_nt_tile_param.restype = ci
         lib.gemm_nt_tile_param.argtypes = [ci]
+        lib.gemm_nt_fp8.restype = ci
+        lib.gemm_nt_fp8.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci]
+        lib.gemm_nt_fp8_check_args.restype = ci
+        lib.gemm_nt_fp8_check_args.argtypes = [vp, vp, vp, ci, ci, ci, ci]
+        lib.gemm_nt_fp8_tile_param.restype = ci
+        lib.gemm_nt_fp8_tile_param.argtypes = [ci]
         _lib = lib
     return _lib
 
@@ -195,7 +203,7 @@ def mfma_probe(sink, workgroups: int, iters: int, random_operands: bool, dtype: 
                                      _stream_handle(stream)))
     if rc != 0:
         raise AttnFwdError(rc, strerror(rc))
-    return float(lib.attn_fwd_mfma_probe_flops(int(workgroups), int(iters)))
+    return float(lib.attn_fwd_mfma_probe_flops_of(int(workgroups), int(iters), int(dtype)))
 
 
 class GemmNtError(RuntimeError):
@@ -232,3 +240,22 @@ def gemm_tile_params() -> dict:
     lib = load_library()
     return {"BM": lib.gemm_nt_tile_param(0), "BN": lib.gemm_nt_tile_param(1), "BK": lib.gemm_nt_tile_param(2),
             "stages": lib.gemm_nt_tile_param(3), "threads": lib.gemm_nt_tile_param(4)}
+
+
+def gemm_nt_fp8_raw(a, b, c, M, N, K, stream, out_dtype) -> int:
+    """The C call itself; returns its code without raising."""
+    return int(load_library().gemm_nt_fp8(_ptr(a), _ptr(b), _ptr(c), int(M), int(N), int(K), _stream_handle(stream), int(out_dtype)))
+
+
+def gemm_nt_fp8(a, b, c, M, N, K, stream=None, out_dtype=FP16) -> None:
+    """``gemm_nt_fp8(a, b, c, M, N, K, stream, out_dtype)`` of the C ABI: ``C = A B^T`` for E4M3 bytes
+    ``a`` [M,K], ``b`` [N,K] and a 16-bit ``c`` [M,N] of type ``out_dtype``.  Asynchronous."""
+    rc = gemm_nt_fp8_raw(a, b, c, M, N, K, stream, out_dtype)
+    if rc != 0:
+        raise GemmNtError(rc, load_library().gemm_nt_strerror(rc).decode())
+
+
+def gemm_fp8_tile_params() -> dict:
+    lib = load_library()
+    return {"BM": lib.gemm_nt_fp8_tile_param(0), "BN": lib.gemm_nt_fp8_tile_param(1), "BK": lib.gemm_nt_fp8_tile_param(2),
+            "stages": lib.gemm_nt_fp8_tile_param(3), "threads": lib.gemm_nt_fp8_tile_param(4)}

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libattn_fwd.so")
 
-SOURCES = ["attn_fwd_kernel.hip", "attn_fwd_fp8_kernel.hip", "mfma_probe.hip", "attn_api.cpp", "gemm_nt_kernel.hip", "gemm_api.cpp"]
+SOURCES = ["attn_fwd_kernel.hip", "attn_fwd_fp8_kernel.hip", "mfma_probe.hip", "attn_api.cpp", "gemm_nt_kernel.hip", "gemm_nt_fp8_kernel.hip", "gemm_api.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

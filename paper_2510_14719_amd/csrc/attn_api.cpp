@@ -127,7 +127,7 @@ int attn_fwd_mfma_probe(float* sink, int workgroups, int iters, int random_opera
 {
     if (!sink) return ATTN_FWD_ERR_NULL;
     if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24)) return ATTN_FWD_ERR_SHAPE;
-    if (dtype != ATTN_FWD_FP16 && dtype != ATTN_FWD_BF16) return ATTN_FWD_ERR_SHAPE;
+    if (dtype != ATTN_FWD_FP16 && dtype != ATTN_FWD_BF16 && dtype != ATTN_FWD_PROBE_E4M3) return ATTN_FWD_ERR_SHAPE;
     if (reinterpret_cast<std::uintptr_t>(sink) & 3u) return ATTN_FWD_ERR_ALIGN;
     return mfma_probe_launch(sink, workgroups, iters, random_operands != 0, dtype, stream) == 0 ? ATTN_FWD_OK : ATTN_FWD_ERR_LAUNCH;
 }
@@ -135,7 +135,14 @@ int attn_fwd_mfma_probe(float* sink, int workgroups, int iters, int random_opera
 double attn_fwd_mfma_probe_flops(int workgroups, int iters)
 {
     if (workgroups < 1 || iters < 1) return 0.0;
-    return mfma_probe_flops(workgroups, iters);
+    return mfma_probe_flops(workgroups, iters, ATTN_FWD_FP16);
+}
+
+double attn_fwd_mfma_probe_flops_of(int workgroups, int iters, int dtype)
+{
+    if (workgroups < 1 || iters < 1) return 0.0;
+    if (dtype != ATTN_FWD_FP16 && dtype != ATTN_FWD_BF16 && dtype != ATTN_FWD_PROBE_E4M3) return 0.0;
+    return mfma_probe_flops(workgroups, iters, dtype);
 }
 
 int attn_fwd_mfma_probe_sink_floats(int workgroups)

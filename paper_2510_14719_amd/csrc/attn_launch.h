@@ -58,5 +58,5 @@ int attn_fp8_launch_tile_param(int d, int which);
 // Register-only MFMA stream (mfma_probe.hip): `workgroups` workgroups of mfma_probe_threads() threads,
 // every wave issuing iters * 8 MFMAs of the given element type; one float per thread is written to sink.
 int mfma_probe_launch(float* sink, int workgroups, int iters, int random_operands, int dtype, void* stream);
-double mfma_probe_flops(int workgroups, int iters);
+double mfma_probe_flops(int workgroups, int iters, int dtype);   // dtype 2: E4M3 operands on the 32x32x64 MFMA
 int mfma_probe_threads(void);

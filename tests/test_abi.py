@@ -113,12 +113,18 @@ def test_mfma_probe_validation_needs_no_gpu(lib):
     # 8 waves x iters x 8 MFMAs x 2*32*32*16 flops per workgroup
     assert lib.attn_fwd_mfma_probe_flops(2, 10) == 2 * 8 * 10 * 8 * 32768.0
     assert lib.attn_fwd_mfma_probe_flops(0, 10) == 0.0
+    lib.attn_fwd_mfma_probe_flops_of.restype = ctypes.c_double
+    assert lib.attn_fwd_mfma_probe_flops_of(2, 10, 1) == 2 * 8 * 10 * 8 * 32768.0
+    assert lib.attn_fwd_mfma_probe_flops_of(2, 10, 2) == 2 * 8 * 10 * 8 * 4 * 32768.0     # 32x32x64 on E4M3
+    assert lib.attn_fwd_mfma_probe_flops_of(2, 10, 3) == 0.0
+    assert f(0x10000002, 256, 100, 1, 2, None) == -4                                       # dtype 2 passes the dtype check
 
 
 def test_gemm_header_symbols_are_exported(lib):
     src = re.sub(r"/\*.*?\*/", "", open(GEMM_HEADER).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(gemm_nt\w*)\s*\(", src)))
-    assert {"gemm_nt", "gemm_nt_f16", "gemm_nt_bf16", "gemm_nt_check_args", "gemm_nt_strerror", "gemm_nt_tile_param"} <= set(names)
+    assert {"gemm_nt", "gemm_nt_f16", "gemm_nt_bf16", "gemm_nt_check_args", "gemm_nt_strerror", "gemm_nt_tile_param",
+            "gemm_nt_fp8", "gemm_nt_fp8_check_args", "gemm_nt_fp8_tile_param"} <= set(names)
     for n in names:
         assert hasattr(lib, n), "library does not export %s" % n
 
@@ -148,3 +154,26 @@ def test_gemm_argument_validation_needs_no_gpu(lib):
         assert len(lib.gemm_nt_strerror(code)) > 3
     bm, bn, bk, st, th = (lib.gemm_nt_tile_param(w) for w in range(5))
     assert st * (bm + bn) * bk * 2 <= 160 * 1024 and th % 64 == 0 and lib.gemm_nt_tile_param(9) == -1
+
+
+def test_gemm_fp8_argument_validation_needs_no_gpu(lib):
+    a, b, c = 0x10000000, 0x20000000, 0x30000000
+    f = lib.gemm_nt_fp8_check_args
+    assert f(a, b, c, 256, 256, 64, 0) == 0
+    assert f(a, b, c, 1, 1, 128, 1) == 0
+    assert f(0, b, c, 256, 256, 64, 0) == -1
+    assert f(a, 0, c, 256, 256, 64, 0) == -1
+    assert f(a, b, c, 0, 256, 64, 0) == -2
+    assert f(a, b, c, 256, 256, 32, 0) == -2          # K must be a multiple of 64
+    assert f(a, b, c, 256, 256, 96, 0) == -2
+    assert f(a, b, c, 256, 256, 64, 2) == -2          # the result is fp16 or bf16
+    assert f(a + 8, b, c, 256, 256, 64, 0) == -4
+    assert f(a, b, c + 1, 256, 256, 64, 0) == -4
+    assert f(a, b, c, 131072, 256, 16384, 0) == -5    # 2 GiB of A
+    assert f(a, 0x100000000, 0x200000000, 65536, 256, 16384, 0) == 0      # 1 GiB of bytes is fine
+    assert f(a, b, a, 256, 256, 64, 0) == -7
+    assert f(a, b, b + 64, 256, 256, 64, 0) == -7
+    assert lib.gemm_nt_fp8(None, None, None, 1, 1, 64, None, 0) == -1
+    assert lib.gemm_nt_fp8(a, b, c, 8, 8, 63, None, 0) == -2
+    bm, bn, bk, st, th = (lib.gemm_nt_fp8_tile_param(w) for w in range(5))
+    assert st * (bm + bn) * bk <= 160 * 1024 and th % 64 == 0 and lib.gemm_nt_fp8_tile_param(9) == -1
