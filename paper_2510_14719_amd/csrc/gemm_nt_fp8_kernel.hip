@@ -33,6 +33,10 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 #ifndef GEMM8_TAIL_READS
 #define GEMM8_TAIL_READS 3
 #endif
+// Which MFMA slots carry the copies: the odd ones (1) or the even ones (0).
+#ifndef GEMM8_COPY_PHASE
+#define GEMM8_COPY_PHASE 1
+#endif
 constexpr int H_NW = 8;                 // waves per workgroup, 2 (m) x 4 (n); every wave copies and computes
 constexpr int H_NB = 2;                 // 32-column blocks of C per wave (its rows are 4 blocks)
 constexpr int H_BM = 256, H_BN = 256;   // tile of C per workgroup
@@ -193,7 +197,7 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
             acc[nb][mb] = mfma_e4m3(whole(cur.bn[nb]), whole(cur.am[mb]), acc[nb][mb]);
             __builtin_amdgcn_sched_barrier(0);
             read_half(nxt, jn, next_read++);
-            if (q & 1) {
+            if ((q & 1) == GEMM8_COPY_PHASE) {
                 if (cs >= 0) issue_piece(cs, q >> 1);
             } else {
                 read_half(nxt, jn, next_read++);

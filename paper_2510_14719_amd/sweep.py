@@ -3,8 +3,8 @@ and the MMA issue depth P, Section 5.5, and of its ablation, Section 5.6).
 
 The knobs are compile-time constants of the HIP sources, so a sweep is two steps:
 
-    python -m paper_2510_14719_amd.sweep build [--op attn|gemm]     # anywhere hipcc runs (no GPU needed)
-    python -m paper_2510_14719_amd.sweep run   [--op attn|gemm] ...  # on the GPU: times every built variant
+    python -m paper_2510_14719_amd.sweep build [--op attn|gemm|...] # anywhere hipcc runs (no GPU needed)
+    python -m paper_2510_14719_amd.sweep run   [--op attn|gemm|...] ...  # on the GPU: times every built variant
 
 ``build`` compiles one shared library per grid point into ``sweep_variants/`` next to this file; ``run``
 loads each through ctypes, checks a few sampled outputs of every variant against the default build's
@@ -24,6 +24,8 @@ What the axes stand for on gfx950:
   gemm       GEMM_STAGES        depth of the LDS ring (the paper's D): 4 or 5
              GEMM_COMPUTE_WAVES waves per workgroup: 8 x (128 x 64) or 4 x (128 x 128)
              GEMM_TAIL_READS    LDS requests allowed in flight across the tile boundary
+  gemm_fp8   GEMM8_STAGES, GEMM8_TAIL_READS   the same for the 8-bit-float kernel
+             GEMM8_COPY_PHASE   copies behind the odd (1) or the even (0) MFMAs of a K tile
 """
 from __future__ import annotations
 
@@ -42,9 +44,11 @@ GRIDS = {
     "attn_causal": {"ATTN_PERSISTENT": [0, 1], "ATTN_FWIN": [2, 4]},
     "attn_fp8": {"ATTN8_FWIN": [1, 2, 3], "ATTN8_INTERLEAVE": [1, 0], "ATTN8_STAGES": [4, 8], "ATTN8_COPIES_IN_PASS": [1, 0]},
     "gemm": {"GEMM_STAGES": [4, 5], "GEMM_COMPUTE_WAVES": [8, 4], "GEMM_TAIL_READS": [0, 3]},
+    "gemm_fp8": {"GEMM8_STAGES": [4, 5], "GEMM8_TAIL_READS": [0, 3, 6], "GEMM8_COPY_PHASE": [1, 0]},
 }
 DEFAULTS = {"ATTN8_FWIN": 2, "ATTN8_INTERLEAVE": 1, "ATTN8_STAGES": 4, "ATTN8_COPIES_IN_PASS": 1, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
-            "GEMM_STAGES": 4, "GEMM_COMPUTE_WAVES": 8, "GEMM_TAIL_READS": 3}
+            "GEMM_STAGES": 4, "GEMM_COMPUTE_WAVES": 8, "GEMM_TAIL_READS": 3,
+            "GEMM8_STAGES": 4, "GEMM8_TAIL_READS": 3, "GEMM8_COPY_PHASE": 1}
 
 
 def grid_points(op: str):
@@ -87,6 +91,8 @@ def _load(path):
     lib.attn_fwd_fp8.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, cf, ci, vp, ci]
     lib.gemm_nt.restype = ci
     lib.gemm_nt.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci]
+    lib.gemm_nt_fp8.restype = ci
+    lib.gemm_nt_fp8.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci]
     return lib
 
 
@@ -110,6 +116,15 @@ def cmd_run(args) -> int:
             out = torch.empty((M, N), dtype=torch.int16, device="cuda")
             flops, what = 2.0 * M * N * K, "gemm_nt M=N=8192 K=%d fp16" % K
             call = lambda lib: lib.gemm_nt(a.data_ptr(), b.data_ptr(), out.data_ptr(), M, N, K, stream, 0)
+            view = lambda: out.view(torch.float16)[::509, ::263].float().cpu().numpy()
+        elif op == "gemm_fp8":
+            M = N = 8192
+            K = args.K
+            a_bits, b_bits = I.make_ab(M, N, K, I.E4M3, 7000 + K)
+            a, b = torch.from_numpy(a_bits).cuda(), torch.from_numpy(b_bits).cuda()
+            out = torch.empty((M, N), dtype=torch.int16, device="cuda")
+            flops, what = 2.0 * M * N * K, "gemm_nt_fp8 M=N=8192 K=%d" % K
+            call = lambda lib: lib.gemm_nt_fp8(a.data_ptr(), b.data_ptr(), out.data_ptr(), M, N, K, stream, 0)
             view = lambda: out.view(torch.float16)[::509, ::263].float().cpu().numpy()
         elif op == "attn_fp8":
             w = I.FP8_WORKLOADS[args.fp8_workload]
