@@ -19,6 +19,7 @@
 // and runs of four consecutive n (8-byte stores).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "gemm_launch.h"
 #include "gfx950_prims.h"
@@ -185,11 +186,12 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
     // MFMA go requests for the next tile's fragments into `nxt` and, behind every second one, a copy of
     // the stage three tiles ahead: 12 LDS requests and 4 copies over 8 slots of 64 cycles.  Stage j+1 is
     // complete at barrier j, which makes the early requests legal.
-    auto tile = [&](int j, const TileFrags& cur, TileFrags& nxt) __attribute__((always_inline)) {
-        wait_next_stage(j);
+    auto tile = [&](int j, const TileFrags& cur, TileFrags& nxt, auto steady_tag) __attribute__((always_inline)) {
+        constexpr bool STEADY = decltype(steady_tag)::value;   // j + H_AHEAD < nk is known: no tests in the tile
+        if (STEADY) wait_vmcnt<(H_AHEAD - 2) * H_LPG>(); else wait_next_stage(j);
         __builtin_amdgcn_s_barrier();
-        const int cs = j + H_AHEAD < nk ? j + H_AHEAD : -1;   // the stage whose copies go out during this tile
-        const int jn = j + 1 < nk ? j + 1 : j;                // (the last tile re-reads itself: harmless, unused)
+        const int cs = STEADY || j + H_AHEAD < nk ? j + H_AHEAD : -1;   // the stage whose copies go out during this tile
+        const int jn = STEADY || j + 1 < nk ? j + 1 : j;                // (the last tile re-reads itself: harmless, unused)
         int next_read = 0;
 #pragma unroll
         for (int q = 0; q < MFMAS_PER_TILE; ++q) {
@@ -198,7 +200,7 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
             __builtin_amdgcn_sched_barrier(0);
             read_half(nxt, jn, next_read++);
             if ((q & 1) == GEMM8_COPY_PHASE) {
-                if (cs >= 0) issue_piece(cs, q >> 1);
+                if (STEADY || cs >= 0) issue_piece(cs, q >> 1);
             } else {
                 read_half(nxt, jn, next_read++);
             }
@@ -215,16 +217,27 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
     for (int i = 0; i < READS_PER_TILE; ++i) read_half(X, 0, i);
     __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
     // Tiles in pairs so that the two fragment sets swap roles without a register copy; bottom-tested
-    // loop, an odd last tile peeled off.
+    // loops, an odd last tile peeled off.  While a tile H_AHEAD ahead exists ("steady") a tile body has
+    // no tests at all; the last H_AHEAD tiles and short products take the body that tests what is left
+    // to copy and to wait for (a wave-uniform branch around every copy costs 2 % at K = 8192).
+    typedef std::integral_constant<bool, true> steady_t;
+    typedef std::integral_constant<bool, false> draining_t;
     int j = 0;
-    if (nk >= 2) {
+    if (nk >= H_AHEAD + 2) {
         do {
-            tile(j, X, Y);
-            tile(j + 1, Y, X);
+            tile(j, X, Y, steady_t());
+            tile(j + 1, Y, X, steady_t());
+            j += 2;
+        } while (j + 1 + H_AHEAD < nk);
+    }
+    if (j + 1 < nk) {
+        do {
+            tile(j, X, Y, draining_t());
+            tile(j + 1, Y, X, draining_t());
             j += 2;
         } while (j + 1 < nk);
     }
-    if (j < nk) tile(j, X, Y);
+    if (j < nk) tile(j, X, Y, draining_t());
 
     // ---- epilogue: lane holds row m of C and, per accumulator register quad, four consecutive n
     const bool vec_ok = (N & 3) == 0 && (reinterpret_cast<uintptr_t>(C) & 7) == 0;

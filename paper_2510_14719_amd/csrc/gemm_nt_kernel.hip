@@ -30,6 +30,7 @@
 //   mapped to rows (lane -> row L%16) instead of to the 16-byte columns of a row: 0.96.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "gemm_launch.h"
 #include "gfx950_prims.h"
@@ -208,14 +209,15 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
     unsigned long long dbg_acc[8] = {};
     const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime(), ct0 = __builtin_readcyclecounter();
 #endif
-    auto tile = [&](int j, const TileFrags& cur, TileFrags& nxt) __attribute__((always_inline)) {
+    auto tile = [&](int j, const TileFrags& cur, TileFrags& nxt, auto steady_tag) __attribute__((always_inline)) {
+        constexpr bool STEADY = decltype(steady_tag)::value;   // j + G_AHEAD < nk is known: no tests in the tile
         GSTAMP(t0);
-        wait_next_stage(j);
+        if (STEADY) wait_vmcnt<(G_AHEAD - 2) * G_LPG>(); else wait_next_stage(j);
         GSTAMP(t1);
         __builtin_amdgcn_s_barrier();
         GSTAMP(t2);
-        const int cs = j + G_AHEAD < nk ? j + G_AHEAD : -1;   // the stage whose copies go out during this tile
-        const int jn = j + 1 < nk ? j + 1 : j;                             // (the last tile re-reads itself: harmless, unused)
+        const int cs = STEADY || j + G_AHEAD < nk ? j + G_AHEAD : -1;   // the stage whose copies go out during this tile
+        const int jn = STEADY || j + 1 < nk ? j + 1 : j;                // (the last tile re-reads itself: harmless, unused)
         constexpr int COPY_EVERY = MFMAS_PER_TILE / G_LPG;
         int next_frag = 0;
 #pragma unroll
@@ -224,7 +226,7 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
             acc[nb][mb] = E::mfma(cur.bn[ks][nb], cur.am[ks][mb], acc[nb][mb]);
             __builtin_amdgcn_sched_barrier(0);
             if (q % COPY_EVERY == COPY_EVERY - 1) {
-                if (cs >= 0) issue_piece(cs, q / COPY_EVERY);
+                if (STEADY || cs >= 0) issue_piece(cs, q / COPY_EVERY);
             } else if (next_frag < FRAGS_PER_TILE) {
                 read_frag(nxt, jn, next_frag);
                 ++next_frag;
@@ -245,17 +247,28 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
     for (int i = 0; i < FRAGS_PER_TILE; ++i) read_frag(X, 0, i);
     __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
     // Tiles are taken in pairs so that the two fragment sets swap roles without a register copy; the
-    // loop is bottom-tested (with the exit test at the top the accumulators would be copied every
-    // iteration) and an odd last tile is peeled off.
+    // loops are bottom-tested (with the exit test at the top the accumulators would be copied every
+    // iteration) and an odd last tile is peeled off.  While a tile G_AHEAD ahead exists ("steady") a
+    // tile body has no tests at all; the last G_AHEAD tiles and short products take the body that tests
+    // what is left to copy and to wait for.
+    typedef std::integral_constant<bool, true> steady_t;
+    typedef std::integral_constant<bool, false> draining_t;
     int j = 0;
-    if (nk >= 2) {
+    if (nk >= G_AHEAD + 2) {
         do {
-            tile(j, X, Y);
-            tile(j + 1, Y, X);
+            tile(j, X, Y, steady_t());
+            tile(j + 1, Y, X, steady_t());
+            j += 2;
+        } while (j + 1 + G_AHEAD < nk);
+    }
+    if (j + 1 < nk) {
+        do {
+            tile(j, X, Y, draining_t());
+            tile(j + 1, Y, X, draining_t());
             j += 2;
         } while (j + 1 < nk);
     }
-    if (j < nk) tile(j, X, Y);
+    if (j < nk) tile(j, X, Y, draining_t());
 
 #ifdef GEMM_TIMING
     if (blockIdx.x < 256 && lane == 0) {
