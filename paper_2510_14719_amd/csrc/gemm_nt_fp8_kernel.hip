@@ -38,8 +38,14 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 #ifndef GEMM8_COPY_PHASE
 #define GEMM8_COPY_PHASE 1
 #endif
-constexpr int H_NW = 8;                 // waves per workgroup, 2 (m) x 4 (n); every wave copies and computes
-constexpr int H_NB = 2;                 // 32-column blocks of C per wave (its rows are 4 blocks)
+// Waves per workgroup: 8 (two per SIMD, 128 x 64 of C each) or 4 (one per SIMD, 128 x 128 each, a third
+// fewer LDS reads, accumulators in the AGPRs).
+#ifndef GEMM8_WAVES
+#define GEMM8_WAVES 8
+#endif
+constexpr int H_NW = GEMM8_WAVES;       // waves per workgroup, 2 (m) x H_NW/2 (n); every wave copies and computes
+constexpr int H_NB = 8 / (H_NW / 2);    // 32-column blocks of C per wave (its rows are 4 blocks)
+static_assert(H_NW == 8 || H_NW == 4, "wave layout is 2 x (H_NW / 2)");
 constexpr int H_BM = 256, H_BN = 256;   // tile of C per workgroup
 constexpr int H_BK = 64;                // K tile, elements = bytes per row
 #ifndef GEMM8_STAGES
@@ -84,7 +90,7 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int lr = lane & 31, g = lane >> 5;
-    const int wm = wave & 1, wn = wave >> 1;          // the wave's 128 x 64 block inside the tile
+    const int wm = wave & 1, wn = wave >> 1;          // the wave's 128 x (32 H_NB) block inside the tile
 
     int tm, tn;
     tile_coords8(__builtin_amdgcn_readfirstlane(tile_schedule(ntm * ntn, (int)gridDim.x, (int)blockIdx.x, 0)), ntm, ntn, tm, tn);
@@ -153,18 +159,21 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
     struct TileFrags { i32x4 bn[H_NB][2]; i32x4 am[4][2]; };
     constexpr int READS_PER_TILE = 2 * (H_NB + 4), MFMAS_PER_TILE = 4 * H_NB;
     // Half-fragment request number i of a tile, in the order the MFMAs need them:
-    // bn0, am0, bn1, am1, am2, am3 (MFMA q multiplies am[q / 2] with bn[q % 2]).
+    // bn0, am0, bn1 ... bn(H_NB-1), am1, am2, am3 (MFMA q multiplies am[q / H_NB] with bn[q % H_NB]).
     auto read_half = [&](TileFrags& t, int s, int i) __attribute__((always_inline)) {
         const int f = i >> 1, h = i & 1;
         if (f == 0) t.bn[0][h] = read_bn(s, h, 0);
         else if (f == 1) t.am[0][h] = read_am(s, h, 0);
-        else if (f == 2) t.bn[1][h] = read_bn(s, h, 1);
-        else t.am[f - 2][h] = read_am(s, h, f - 2);
+        else if (f <= H_NB) t.bn[f - 1][h] = read_bn(s, h, f - 1);
+        else t.am[f - H_NB][h] = read_am(s, h, f - H_NB);
     };
     auto whole = [](const i32x4 (&x)[2]) __attribute__((always_inline)) -> i32x8 {
         return __builtin_shufflevector(x[0], x[1], 0, 1, 2, 3, 4, 5, 6, 7);
     };
-    static_assert(H_LPG * 2 == MFMAS_PER_TILE && READS_PER_TILE == 12, "slot plan of `tile`");
+    // Slot plan of `tile`: a copy behind every second MFMA, the requests spread evenly over all slots
+    // (the slots that carry a copy take the smaller share).
+    constexpr int READS_LO = READS_PER_TILE / MFMAS_PER_TILE, READS_HI = (READS_PER_TILE + MFMAS_PER_TILE - 1) / MFMAS_PER_TILE;
+    static_assert(H_LPG * 2 == MFMAS_PER_TILE && (READS_LO + READS_HI) * (MFMAS_PER_TILE / 2) == READS_PER_TILE, "slot plan of `tile`");
 
     // Own copies of stage j+1 complete: only the stages after it stay in flight.
     auto wait_next_stage = [&](int j) __attribute__((always_inline)) {
@@ -182,9 +191,10 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
     else if (nk > 2) wait_vmcnt<2 * H_LPG>(); else if (nk > 1) wait_vmcnt<H_LPG>(); else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
 
-    // One K tile: 8 MFMAs on the fragments in `cur` (requested during the previous tile).  Behind each
-    // MFMA go requests for the next tile's fragments into `nxt` and, behind every second one, a copy of
-    // the stage three tiles ahead: 12 LDS requests and 4 copies over 8 slots of 64 cycles.  Stage j+1 is
+    // One K tile: 8 MFMAs (16 with four waves) on the fragments in `cur` (requested during the previous
+    // tile).  Behind each MFMA go requests for the next tile's fragments into `nxt` and, behind every second
+    // one, a copy of the stage three tiles ahead: 12 LDS requests and 4 copies over 8 slots of 64 cycles
+    // (16 and 8 over 16).  Stage j+1 is
     // complete at barrier j, which makes the early requests legal.
     auto tile = [&](int j, const TileFrags& cur, TileFrags& nxt, auto steady_tag) __attribute__((always_inline)) {
         constexpr bool STEADY = decltype(steady_tag)::value;   // j + H_AHEAD < nk is known: no tests in the tile
@@ -198,12 +208,10 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
             const int mb = q / H_NB, nb = q % H_NB;
             acc[nb][mb] = mfma_e4m3(whole(cur.bn[nb]), whole(cur.am[mb]), acc[nb][mb]);
             __builtin_amdgcn_sched_barrier(0);
-            read_half(nxt, jn, next_read++);
-            if ((q & 1) == GEMM8_COPY_PHASE) {
-                if (STEADY || cs >= 0) issue_piece(cs, q >> 1);
-            } else {
-                read_half(nxt, jn, next_read++);
-            }
+            const bool copy_slot = (q & 1) == GEMM8_COPY_PHASE;
+#pragma unroll
+            for (int r = 0; r < (copy_slot ? READS_LO : READS_HI); ++r) read_half(nxt, jn, next_read++);
+            if (copy_slot && (STEADY || cs >= 0)) issue_piece(cs, q >> 1);
             __builtin_amdgcn_sched_barrier(0);
         }
         // The fragments the next tile needs first were requested first and have landed; the last few
