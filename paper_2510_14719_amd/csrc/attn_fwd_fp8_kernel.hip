@@ -18,8 +18,11 @@
 // 3.3): a stage is overwritten only after every wave has passed the barrier that follows its last
 // read of it.  Stage s holds K tile s+2 and V tile s, the pair that iteration s+1 reads.  Barrier j
 // makes stage j visible, one stage more than iteration j reads, so the last tile's U needs no
-// barrier of its own.  (Measured on MI355X: a deeper ring, requesting the next tile's first
-// fragments before the barrier, and spreading the copies over the pass each cost 1-3 %.)
+// barrier of its own.  In the steady state a wave issues its copies of a stage one by one behind
+// the first MFMAs of the pass (+3 % over issuing them as a block after the barrier; a copy
+// instruction holds its wave for 60-90 cycles, which a 64-cycle MFMA of the same wave covers).
+// (Measured on MI355X: a deeper ring and requesting the next tile's first fragments before the
+// barrier each cost 1-3 %; four waves of 32 query rows per workgroup instead of eight: -20 %.)
 //
 // What changes with the element type:
 //  * Both contractions use the 32x32x64 MFMA on 8-bit operands (32 bytes per lane and operand):
