@@ -124,6 +124,37 @@ def test_extreme_values_do_not_overflow_the_accumulator(env):
     assert np.isinf(c16).all() and np.array_equal(np.sign(c16), np.sign(ref))
 
 
+def test_subnormal_operands_and_signed_zeros(env):
+    # every product of two E4M3 subnormals (multiples of 2^-9) is a multiple of 2^-18 below 2^-12: the sums
+    # over K = 64 stay exact in any summation frame that keeps 13 bits below its largest term, and in fp16
+    _, _, G = env
+    rng = np.random.Generator(np.random.Philox(21))
+    M, N, K = 70, 90, 64
+    a = rng.integers(0, 8, size=(M, K)).astype(np.uint8) | (rng.integers(0, 2, size=(M, K)).astype(np.uint8) << 7)
+    b = rng.integers(0, 8, size=(N, K)).astype(np.uint8) | (rng.integers(0, 2, size=(N, K)).astype(np.uint8) << 7)
+    ref = G.gemm_nt(a, b, I.E4M3)
+    c = run_gpu(env, a, b, I.FP16).double().cpu().numpy()
+    assert np.abs(ref).max() > 0 and np.array_equal(c, ref)
+
+
+def test_nan_operands_poison_their_row_and_column_only(env):
+    _, _, G = env
+    M, N, K = 260, 300, 128
+    a, b = I.make_ab(M, N, K, I.E4M3, seed=33)
+    a[17, 5] = 0x7F                      # NaN in row 17 of A
+    b[258, 127] = 0xFF                   # NaN in row 258 of B = column 258 of C
+    ref = G.gemm_nt(a, b, I.E4M3)
+    c = run_gpu(env, a, b, I.FP16).double().cpu().numpy()
+    want_nan = np.zeros((M, N), dtype=bool)
+    want_nan[17, :] = True
+    want_nan[:, 258] = True
+    assert np.array_equal(np.isnan(ref), want_nan) and np.array_equal(np.isnan(c), want_nan)
+    ok = ~want_nan
+    s_abs = magnitudes(env, np.where(a == 0x7F, 0, a).astype(np.uint8)) @ magnitudes(env, np.where(b == 0xFF, 0, b).astype(np.uint8)).T
+    err = np.abs(c[ok] - ref[ok])
+    assert (err <= 1.01 * U[I.FP16] * np.abs(ref[ok]) + 2.0 ** -14 * s_abs[ok]).all()
+
+
 @pytest.mark.parametrize("K", [256, 8192, 16384])
 def test_paper_sweep_sizes_sampled(env, K):
     # M = N = 8192 (the benchmark's launch configuration), sampled entries against the oracle
