@@ -71,6 +71,14 @@ int gemm_nt_check_args(const void *a, const void *b, const void *c, int M, int N
  */
 int gemm_nt_fp8(const void *a, const void *b, void *c, int M, int N, int K, void *stream, int out_dtype);
 
+/*
+ * The same call with the kernel configuration chosen by the caller instead of by K (for tests and
+ * measurements; every configuration computes the same product): 0 = as gemm_nt_fp8, 1 = 8 waves of 128 x 64,
+ * 2 = the same with the copies of two consecutive K tiles issued together, 3 = 4 waves of 128 x 128,
+ * 4 = the same with paired copies.  GEMM_NT_ERR_SHAPE for any other value.
+ */
+int gemm_nt_fp8_config(const void *a, const void *b, void *c, int M, int N, int K, void *stream, int out_dtype, int config);
+
 /* Host-only argument check: what gemm_nt_fp8 would return before launching. */
 int gemm_nt_fp8_check_args(const void *a, const void *b, const void *c, int M, int N, int K, int out_dtype);
 
@@ -83,7 +91,7 @@ const char *gemm_nt_strerror(int code);
  */
 int gemm_nt_tile_param(int which);
 
-/* The same for the kernel behind gemm_nt_fp8. */
+/* The same for the kernel behind gemm_nt_fp8 (the configuration a large K takes). */
 int gemm_nt_fp8_tile_param(int which);
 
 #ifdef __cplusplus

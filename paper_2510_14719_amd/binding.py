@@ -85,6 +85,8 @@ def load_library() -> ctypes.CDLL:
         lib.gemm_nt_tile_param.argtypes = [ci]
         lib.gemm_nt_fp8.restype = ci
         lib.gemm_nt_fp8.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci]
+        lib.gemm_nt_fp8_config.restype = ci
+        lib.gemm_nt_fp8_config.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci, ci]
         lib.gemm_nt_fp8_check_args.restype = ci
         lib.gemm_nt_fp8_check_args.argtypes = [vp, vp, vp, ci, ci, ci, ci]
         lib.gemm_nt_fp8_tile_param.restype = ci
@@ -242,15 +244,20 @@ def gemm_tile_params() -> dict:
             "stages": lib.gemm_nt_tile_param(3), "threads": lib.gemm_nt_tile_param(4)}
 
 
-def gemm_nt_fp8_raw(a, b, c, M, N, K, stream, out_dtype) -> int:
-    """The C call itself; returns its code without raising."""
-    return int(load_library().gemm_nt_fp8(_ptr(a), _ptr(b), _ptr(c), int(M), int(N), int(K), _stream_handle(stream), int(out_dtype)))
+def gemm_nt_fp8_raw(a, b, c, M, N, K, stream, out_dtype, config=None) -> int:
+    """The C call itself (``gemm_nt_fp8``, or ``gemm_nt_fp8_config`` when a configuration is given); returns
+    its code without raising."""
+    lib = load_library()
+    if config is None:
+        return int(lib.gemm_nt_fp8(_ptr(a), _ptr(b), _ptr(c), int(M), int(N), int(K), _stream_handle(stream), int(out_dtype)))
+    return int(lib.gemm_nt_fp8_config(_ptr(a), _ptr(b), _ptr(c), int(M), int(N), int(K), _stream_handle(stream), int(out_dtype), int(config)))
 
 
-def gemm_nt_fp8(a, b, c, M, N, K, stream=None, out_dtype=FP16) -> None:
+def gemm_nt_fp8(a, b, c, M, N, K, stream=None, out_dtype=FP16, config=None) -> None:
     """``gemm_nt_fp8(a, b, c, M, N, K, stream, out_dtype)`` of the C ABI: ``C = A B^T`` for E4M3 bytes
-    ``a`` [M,K], ``b`` [N,K] and a 16-bit ``c`` [M,N] of type ``out_dtype``.  Asynchronous."""
-    rc = gemm_nt_fp8_raw(a, b, c, M, N, K, stream, out_dtype)
+    ``a`` [M,K], ``b`` [N,K] and a 16-bit ``c`` [M,N] of type ``out_dtype``.  Asynchronous.  With ``config``
+    the call goes to ``gemm_nt_fp8_config``."""
+    rc = gemm_nt_fp8_raw(a, b, c, M, N, K, stream, out_dtype, config)
     if rc != 0:
         raise GemmNtError(rc, load_library().gemm_nt_strerror(rc).decode())
 

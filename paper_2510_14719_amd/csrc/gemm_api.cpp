@@ -57,12 +57,18 @@ int gemm_nt_fp8_check_args(const void* a, const void* b, const void* c, int M, i
     return GEMM_NT_OK;
 }
 
-int gemm_nt_fp8(const void* a, const void* b, void* c, int M, int N, int K, void* stream, int out_dtype)
+int gemm_nt_fp8_config(const void* a, const void* b, void* c, int M, int N, int K, void* stream, int out_dtype, int config)
 {
     const int rc = gemm_nt_fp8_check_args(a, b, c, M, N, K, out_dtype);
     if (rc != GEMM_NT_OK) return rc;
-    GemmLaunchArgs g{a, b, c, M, N, K, out_dtype, stream};
+    if (config < 0 || config > 4) return GEMM_NT_ERR_SHAPE;
+    GemmLaunchArgs g{a, b, c, M, N, K, out_dtype, stream, config};
     return gemm_fp8_launch(g) == 0 ? GEMM_NT_OK : GEMM_NT_ERR_LAUNCH;
+}
+
+int gemm_nt_fp8(const void* a, const void* b, void* c, int M, int N, int K, void* stream, int out_dtype)
+{
+    return gemm_nt_fp8_config(a, b, c, M, N, K, stream, out_dtype, 0);
 }
 
 int gemm_nt_f16(const void* a, const void* b, void* c, int M, int N, int K, void* stream)

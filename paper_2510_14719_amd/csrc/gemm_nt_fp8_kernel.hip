@@ -3,13 +3,21 @@
 // bf16 (RNE).  The paper measures its matrix multiplication in FP16 and in FP8 (Section 5.2); this is
 // the FP8 one.
 //
-// Same organisation as the 16-bit kernel: a 256 x 256 tile of C per workgroup of 8 waves, a wave owns
-// 128 (m) x 64 (n) = 8 accumulator blocks, both operand tiles travel global -> LDS with direct-to-LDS
-// loads through a ring of 4 stages (the aref ring of Section 3.3; s_waitcnt vmcnt plus one s_barrier
-// per K tile stand in for the full/empty credits), every wave copies its share three K tiles ahead.
-// The K tile is 64 elements = 64 bytes per row, so a stage has the same byte geometry as in the 16-bit
-// kernel (16-row pieces of 1 KiB, row-major, the 16-byte columns of row r rotated by (r/4)%4), and
-// one K tile is one k-step of the 32x32x64 MFMA: 8 MFMAs of 64 cycles per wave and tile.
+// Same organisation as the 16-bit kernel: a 256 x 256 tile of C per workgroup, both operand tiles travel
+// global -> LDS with direct-to-LDS loads through a ring of stages (the aref ring of Section 3.3;
+// s_waitcnt vmcnt plus one s_barrier per K tile stand in for the full/empty credits), every wave copies
+// its share several K tiles ahead.  The K tile is 64 elements = 64 bytes per row, so a stage has the same
+// byte geometry as in the 16-bit kernel (16-row pieces of 1 KiB, row-major, the 16-byte columns of row r
+// rotated by (r/4)%4), and one K tile is one k-step of the 32x32x64 MFMA (64 cycles each).
+//
+// Two shapes of the workgroup are compiled, and the launcher picks by K:
+//   short products: 8 waves (two per SIMD), a wave owns 128 (m) x 64 (n) = 8 accumulator blocks; ring of 4
+//     stages, one stage copied per tile, three tiles ahead;
+//   K >= 2048: 4 waves (one per SIMD), a wave owns 128 x 128 = 16 accumulator blocks in the AGPRs; ring of 5
+//     stages with PAIRED copies: a 64-byte K tile asks the L2 for half a memory line, and what limits this
+//     kernel is the request path from the L2 into the CU, so two consecutive stages are copied together,
+//     piece by piece, at every second tile: the two halves of a line are requested back to back and the L1
+//     merges them (43 % fewer L2 requests, +6-8 % at K = 8192 ... 16384).
 //
 // A lane's operand of that MFMA is 32 bytes of one row.  Which 32 of the row's 64 k a lane holds does
 // not matter for a sum over k as long as both operands agree: lane (row, g) takes 16-byte columns
@@ -38,29 +46,33 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 #ifndef GEMM8_COPY_PHASE
 #define GEMM8_COPY_PHASE 1
 #endif
-// Waves per workgroup: 8 (two per SIMD, 128 x 64 of C each) or 4 (one per SIMD, 128 x 128 each, a third
-// fewer LDS reads, accumulators in the AGPRs).
-#ifndef GEMM8_WAVES
-#define GEMM8_WAVES 8
+// Kernel configuration, fixed at compile time for the sweep harness or chosen per call by K (0):
+//   1: 8 waves (two per SIMD, 128 x 64 of C each), one stage copied per tile, three tiles ahead
+//   2: 8 waves, paired copies (see below)
+//   3: 4 waves (one per SIMD, 128 x 128 each, a third fewer LDS reads, accumulators in the AGPRs)
+//   4: 4 waves, paired copies
+// Paired copies: the copies of two consecutive stages are issued together, piece by piece, at every second
+// tile, so that the two 64-byte halves of a 128-byte memory line are requested back to back and the L1
+// merges them into one request to the L2 (measured: 43 % fewer L2 requests); five stages, copies four and
+// five tiles ahead.
+#ifndef GEMM8_CONFIG
+#define GEMM8_CONFIG 0
 #endif
-constexpr int H_NW = GEMM8_WAVES;       // waves per workgroup, 2 (m) x H_NW/2 (n); every wave copies and computes
-constexpr int H_NB = 8 / (H_NW / 2);    // 32-column blocks of C per wave (its rows are 4 blocks)
-static_assert(H_NW == 8 || H_NW == 4, "wave layout is 2 x (H_NW / 2)");
+// Smallest K for which configuration 0 takes the 4-wave paired kernel (below it: 8 waves, unpaired, whose
+// prologue and epilogue overlap better between the two waves of a SIMD).
+constexpr int H_LARGE_K = 2048;
 constexpr int H_BM = 256, H_BN = 256;   // tile of C per workgroup
 constexpr int H_BK = 64;                // K tile, elements = bytes per row
 #ifndef GEMM8_STAGES
 #define GEMM8_STAGES 4
 #endif
-constexpr int H_STAGES = GEMM8_STAGES;
-constexpr int H_AHEAD = H_STAGES - 1;   // copies run this many K tiles ahead of the tile being multiplied
-static_assert(H_STAGES == 4 || H_STAGES == 5, "ring protocol below");
+static_assert(GEMM8_STAGES == 4 || GEMM8_STAGES == 5, "ring protocol below");
 constexpr int H_OPER_BYTES = H_BM * H_BK;            // one operand tile in the LDS (16 KiB)
 constexpr int H_STAGE_BYTES = 2 * H_OPER_BYTES;      // A tile, then B tile
 constexpr int H_PIECES = H_OPER_BYTES / 1024;        // 1 KiB wave-transfers per operand tile (16 rows x 64 B each)
-constexpr int H_PPW = H_PIECES / H_NW;               // ... per wave and operand
-constexpr int H_LPG = 2 * H_PPW;                     // copies a wave issues per stage
 constexpr int H_GROUP_M = 8;                         // tile rows per raster group
-static_assert(H_BM == H_BN && H_PIECES % H_NW == 0, "operand tiles are copied the same way");
+static_assert(H_BM == H_BN, "operand tiles are copied the same way");
+constexpr int stages_of(bool paired) { return paired ? 5 : GEMM8_STAGES; }
 
 // Logical tile -> (tile row, tile column): tile rows in groups of H_GROUP_M, a group walked column by
 // column, so tiles that run at the same time share A and B row panels in the L2.
@@ -78,12 +90,18 @@ __device__ __forceinline__ f32x16 mfma_e4m3(i32x8 a, i32x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
 }
 
-template <int OUT>
-__global__ __launch_bounds__(H_NW * 64)
+template <int OUT, int NW, bool PAIRED>
+__global__ __launch_bounds__(NW * 64)
 void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
                         int M, int N, int K, int ntm, int ntn)
 {
     typedef Elem<OUT> E;
+    static_assert(NW == 8 || NW == 4, "wave layout is 2 x (NW / 2)");
+    constexpr int H_NB = 8 / (NW / 2);           // 32-column blocks of C per wave (its rows are 4 blocks)
+    constexpr int H_STAGES = stages_of(PAIRED);
+    constexpr int H_AHEAD = H_STAGES - 1;        // unpaired: copies run this many K tiles ahead of the tile being multiplied
+    constexpr int H_PPW = H_PIECES / NW;         // 1 KiB pieces per wave and operand
+    constexpr int H_LPG = 2 * H_PPW;             // copies a wave issues per stage
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const unsigned lds_base = (unsigned)(size_t)(LDS_AS void*)smem;
 
@@ -135,6 +153,14 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
 #pragma unroll
         for (int i = 0; i < H_LPG; ++i) issue_piece(s, i);
     };
+    // The same for a stage that may lie past the last K tile: it then fetches the last tile again (its ring
+    // slot is free by the protocol and never read), which keeps the count of copies in flight uniform.
+    auto issue_piece_any = [&](int s, int i) __attribute__((always_inline)) {
+        const unsigned sbase = lds_base + (s % H_STAGES) * H_STAGE_BYTES + wave * (H_PPW * 1024);
+        const size_t koff = (size_t)min(s, nk - 1) * H_BK;
+        if (i < H_PPW) dma16(a_piece[i] + koff, a_voff[i], sbase + i * 1024);
+        else dma16(b_piece[i - H_PPW] + koff, b_voff[i - H_PPW], sbase + H_OPER_BYTES + (i - H_PPW) * 1024);
+    };
 
     // ---- fragments: 32 rows x 64 k of an operand tile; lane l holds row l%32 and the 16-byte columns
     // 2g + h, h = 0, 1 (g = l/32), stored at position column ^ ((row/4)%4) of the row.
@@ -175,6 +201,56 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
     constexpr int READS_LO = READS_PER_TILE / MFMAS_PER_TILE, READS_HI = (READS_PER_TILE + MFMAS_PER_TILE - 1) / MFMAS_PER_TILE;
     static_assert(H_LPG * 2 == MFMAS_PER_TILE && (READS_LO + READS_HI) * (MFMAS_PER_TILE / 2) == READS_PER_TILE, "slot plan of `tile`");
 
+    if constexpr (PAIRED) {
+    // ---- paired copies.  Ring of five stages.  At the barrier of an even tile e the slots of stages e - 1
+    // and e are free (the fragments of tile e were read during tile e - 1, and every wave waited for its
+    // requests before the barrier), and the wave issues its pieces of stages e + 4 and e + 5 alternately,
+    // one behind each MFMA of the tile; odd tiles issue none.  Before barrier j a wave has waited for its own
+    // copies of stage j + 1: what may still be in flight is the pair issued two tiles ago (j even), or the
+    // last piece of stage j + 2 and the pair issued one tile ago (j odd).
+    static_assert(2 * H_LPG == MFMAS_PER_TILE, "one copy behind each MFMA of an even tile");
+#pragma unroll
+    for (int s0 = 0; s0 < 4; ++s0)
+#pragma unroll
+        for (int i = 0; i < H_LPG; ++i) issue_piece_any(s0, i);
+    wait_vmcnt<3 * H_LPG>();                  // stage 0
+    __builtin_amdgcn_s_barrier();
+    auto tile2 = [&](int j, const TileFrags& cur, TileFrags& nxt, auto even_tag) __attribute__((always_inline)) {
+        constexpr bool EVEN = decltype(even_tag)::value;
+        if (EVEN) wait_vmcnt<2 * H_LPG>(); else wait_vmcnt<2 * H_LPG + 1>();
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's reads of stage j are complete
+        __builtin_amdgcn_s_barrier();
+        const int jn = min(j + 1, nk - 1);    // (the last tile re-reads itself: harmless, unused)
+        int next_read = 0;
+#pragma unroll
+        for (int q = 0; q < MFMAS_PER_TILE; ++q) {
+            const int mb = q / H_NB, nb = q % H_NB;
+            acc[nb][mb] = mfma_e4m3(whole(cur.bn[nb]), whole(cur.am[mb]), acc[nb][mb]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int r = 0; r < ((q & 1) ? READS_LO : READS_HI); ++r) read_half(nxt, jn, next_read++);
+            if (EVEN) issue_piece_any(j + 4 + (q & 1), q >> 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    TileFrags X, Y;
+#pragma unroll
+    for (int i = 0; i < READS_PER_TILE; ++i) read_half(X, 0, i);
+    {
+        typedef std::integral_constant<bool, true> even_t;
+        typedef std::integral_constant<bool, false> odd_t;
+        int j = 0;
+        if (nk >= 2) {
+            do {
+                tile2(j, X, Y, even_t());
+                tile2(j + 1, Y, X, odd_t());
+                j += 2;
+            } while (j + 1 < nk);
+        }
+        if (j < nk) tile2(j, X, Y, even_t());
+    }
+    wait_vmcnt<0>();                          // surplus copies past the last tile
+    } else {
     // Own copies of stage j+1 complete: only the stages after it stay in flight.
     auto wait_next_stage = [&](int j) __attribute__((always_inline)) {
         if (H_AHEAD > 3 && j + 3 < nk) wait_vmcnt<2 * H_LPG>();
@@ -247,6 +323,8 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
     }
     if (j < nk) tile(j, X, Y, draining_t());
 
+    }  // !PAIRED
+
     // ---- epilogue: lane holds row m of C and, per accumulator register quad, four consecutive n
     const bool vec_ok = (N & 3) == 0 && (reinterpret_cast<uintptr_t>(C) & 7) == 0;
 #pragma unroll
@@ -273,11 +351,11 @@ void gemm_nt_fp8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict
     }
 }
 
-template <int OUT>
+template <int OUT, int NW, bool PAIRED>
 int launch8(const GemmLaunchArgs& a)
 {
-    constexpr int smem = H_STAGES * H_STAGE_BYTES;
-    auto kern = gemm_nt_fp8_kernel<OUT>;
+    constexpr int smem = stages_of(PAIRED) * H_STAGE_BYTES;
+    auto kern = gemm_nt_fp8_kernel<OUT, NW, PAIRED>;
     static bool attr_set = false;   // idempotent; a race only repeats the call
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
@@ -290,23 +368,38 @@ int launch8(const GemmLaunchArgs& a)
     int M = a.M, N = a.N, K = a.K;
     int ntm = (M + H_BM - 1) / H_BM, ntn = (N + H_BN - 1) / H_BN;
     void* args[] = {&A, &B, &C, &M, &N, &K, &ntm, &ntn};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3((unsigned)(ntm * ntn)), dim3(H_NW * 64),
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3((unsigned)(ntm * ntn)), dim3(NW * 64),
                                          args, smem, (hipStream_t)a.stream);
     return e == hipSuccess ? 0 : -1;
 }
 
+int config_for(int K) { return GEMM8_CONFIG != 0 ? GEMM8_CONFIG : (K >= H_LARGE_K ? 4 : 1); }
+
+template <int OUT>
+int launch8_out(const GemmLaunchArgs& a)
+{
+    switch (a.config != 0 ? a.config : config_for(a.K)) {
+        case 1: return launch8<OUT, 8, false>(a);
+        case 2: return launch8<OUT, 8, true>(a);
+        case 3: return launch8<OUT, 4, false>(a);
+        default: return launch8<OUT, 4, true>(a);
+    }
+}
+
 }  // namespace
 
-int gemm_fp8_launch(const GemmLaunchArgs& a) { return a.dtype == 0 ? launch8<0>(a) : launch8<1>(a); }
+int gemm_fp8_launch(const GemmLaunchArgs& a) { return a.dtype == 0 ? launch8_out<0>(a) : launch8_out<1>(a); }
 
+// Reported for the configuration a large K takes.
 int gemm_fp8_launch_tile_param(int which)
 {
+    const int cfg = config_for(1 << 20);
     switch (which) {
         case 0: return H_BM;
         case 1: return H_BN;
         case 2: return H_BK;
-        case 3: return H_STAGES;
-        case 4: return H_NW * 64;
+        case 3: return stages_of(cfg == 2 || cfg == 4);
+        case 4: return (cfg >= 3 ? 4 : 8) * 64;
         default: return -1;
     }
 }

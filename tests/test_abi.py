@@ -124,7 +124,7 @@ def test_gemm_header_symbols_are_exported(lib):
     src = re.sub(r"/\*.*?\*/", "", open(GEMM_HEADER).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(gemm_nt\w*)\s*\(", src)))
     assert {"gemm_nt", "gemm_nt_f16", "gemm_nt_bf16", "gemm_nt_check_args", "gemm_nt_strerror", "gemm_nt_tile_param",
-            "gemm_nt_fp8", "gemm_nt_fp8_check_args", "gemm_nt_fp8_tile_param"} <= set(names)
+            "gemm_nt_fp8", "gemm_nt_fp8_config", "gemm_nt_fp8_check_args", "gemm_nt_fp8_tile_param"} <= set(names)
     for n in names:
         assert hasattr(lib, n), "library does not export %s" % n
 
@@ -175,5 +175,8 @@ def test_gemm_fp8_argument_validation_needs_no_gpu(lib):
     assert f(a, b, b + 64, 256, 256, 64, 0) == -7
     assert lib.gemm_nt_fp8(None, None, None, 1, 1, 64, None, 0) == -1
     assert lib.gemm_nt_fp8(a, b, c, 8, 8, 63, None, 0) == -2
+    assert lib.gemm_nt_fp8_config(a, b, c, 8, 8, 64, None, 0, 5) == -2     # unknown configuration
+    assert lib.gemm_nt_fp8_config(a, b, c, 8, 8, 64, None, 0, -1) == -2
+    assert lib.gemm_nt_fp8_config(None, b, c, 8, 8, 64, None, 0, 1) == -1
     bm, bn, bk, st, th = (lib.gemm_nt_fp8_tile_param(w) for w in range(5))
     assert st * (bm + bn) * bk <= 160 * 1024 and th % 64 == 0 and lib.gemm_nt_fp8_tile_param(9) == -1

@@ -33,14 +33,14 @@ def env():
     return torch, binding, gemm_ref
 
 
-def run_gpu(env, a, b, out_dtype, pad=512):
+def run_gpu(env, a, b, out_dtype, pad=512, config=None):
     torch, binding, _ = env
     M, K = a.shape
     N = b.shape[0]
     da, db = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()
     buf = torch.full((M * N + 2 * pad,), 0x7B7B, dtype=torch.int16, device="cuda")
     c = buf[pad:pad + M * N]
-    binding.gemm_nt_fp8(da, db, c, M, N, K, out_dtype=out_dtype)
+    binding.gemm_nt_fp8(da, db, c, M, N, K, out_dtype=out_dtype, config=config)
     torch.cuda.synchronize()
     assert bool((buf[:pad] == 0x7B7B).all()) and bool((buf[pad + M * N:] == 0x7B7B).all()), "guard words overwritten"
     return c.view(torch.bfloat16 if out_dtype == I.BF16 else torch.float16).reshape(M, N)
@@ -71,6 +71,23 @@ def test_full_compare(env, M, N, K, out_dtype):
     ref = G.gemm_nt(a, b, I.E4M3)
     c = run_gpu(env, a, b, out_dtype).double().cpu().numpy()
     check(c, ref, magnitudes(env, a) @ magnitudes(env, b).T, out_dtype, "full M%d N%d K%d" % (M, N, K))
+
+
+@pytest.mark.parametrize("config", [1, 2, 3, 4])
+@pytest.mark.parametrize("M,N,K", [(1, 1, 64), (257, 255, 128), (300, 520, 320), (640, 513, 2112), (256, 256, 2048)])
+def test_every_kernel_configuration_in_full(env, M, N, K, config):
+    # gemm_nt_fp8 picks the configuration by K (1 below 2048, 4 from there on); each of the four kernels
+    # must handle every shape: one and two K tiles, odd and even tile counts, overhanging tiles
+    _, _, G = env
+    a, b = I.make_ab(M, N, K, I.E4M3, seed=500 + M + N + K)
+    print("case gemm_fp8 config%d M%d N%d K%d" % (config, M, N, K), flush=True)
+    ref = G.gemm_nt(a, b, I.E4M3)
+    c = run_gpu(env, a, b, I.FP16, config=config).double().cpu().numpy()
+    check(c, ref, magnitudes(env, a) @ magnitudes(env, b).T, I.FP16, "config %d M%d N%d K%d" % (config, M, N, K))
+    if K >= 2048:       # the call without a configuration takes the 4-wave paired kernel here: bit-identical to config 4
+        c0 = run_gpu(env, a, b, I.FP16).double().cpu().numpy()
+        c4 = run_gpu(env, a, b, I.FP16, config=4).double().cpu().numpy()
+        assert np.array_equal(c0, c4)
 
 
 def test_odd_n_uses_scalar_stores(env):
