@@ -46,6 +46,14 @@ enum { GEMM_NT_FP16 = 0, GEMM_NT_BF16 = 1 };
 
 int gemm_nt(const void *a, const void *b, void *c, int M, int N, int K, void *stream, int dtype);
 
+/*
+ * The same call with the kernel configuration chosen by the caller instead of by K (for tests and
+ * measurements; every configuration computes the same product): 0 = as gemm_nt, 1 = 8 waves of 128 x 64,
+ * 2 = the same with the copies of two consecutive K tiles issued together, 3 = 4 waves of 128 x 128,
+ * 4 = the same with paired copies.  GEMM_NT_ERR_SHAPE for any other value.
+ */
+int gemm_nt_config(const void *a, const void *b, void *c, int M, int N, int K, void *stream, int dtype, int config);
+
 /* The same call with the element type in the name. */
 int gemm_nt_f16(const void *a, const void *b, void *c, int M, int N, int K, void *stream);
 int gemm_nt_bf16(const void *a, const void *b, void *c, int M, int N, int K, void *stream);

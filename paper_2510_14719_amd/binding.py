@@ -73,6 +73,8 @@ def load_library() -> ctypes.CDLL:
         lib.attn_fwd_mfma_probe_sink_floats.argtypes = [ci]
         lib.gemm_nt.restype = ci
         lib.gemm_nt.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci]
+        lib.gemm_nt_config.restype = ci
+        lib.gemm_nt_config.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci, ci]
         lib.gemm_nt_f16.restype = ci
         lib.gemm_nt_f16.argtypes = [vp, vp, vp, ci, ci, ci, vp]
         lib.gemm_nt_bf16.restype = ci
@@ -214,12 +216,16 @@ class GemmNtError(RuntimeError):
         self.code = code
 
 
-def gemm_nt_raw(a, b, c, M, N, K, stream, dtype) -> int:
-    """The C call itself; returns its code without raising."""
-    return int(load_library().gemm_nt(_ptr(a), _ptr(b), _ptr(c), int(M), int(N), int(K), _stream_handle(stream), int(dtype)))
+def gemm_nt_raw(a, b, c, M, N, K, stream, dtype, config=None) -> int:
+    """The C call itself (``gemm_nt``, or ``gemm_nt_config`` when a configuration is given); returns its code
+    without raising."""
+    lib = load_library()
+    if config is None:
+        return int(lib.gemm_nt(_ptr(a), _ptr(b), _ptr(c), int(M), int(N), int(K), _stream_handle(stream), int(dtype)))
+    return int(lib.gemm_nt_config(_ptr(a), _ptr(b), _ptr(c), int(M), int(N), int(K), _stream_handle(stream), int(dtype), int(config)))
 
 
-def gemm_nt(a, b, c, M, N, K, stream=None, dtype=None) -> None:
+def gemm_nt(a, b, c, M, N, K, stream=None, dtype=None, config=None) -> None:
     """``gemm_nt(a, b, c, M, N, K, stream, dtype)`` of the C ABI: ``C = A B^T`` for ``a`` [M,K], ``b`` [N,K].
 
     ``dtype`` defaults to the element type of ``a``.  Asynchronous: the kernel is enqueued on
@@ -233,7 +239,7 @@ def gemm_nt(a, b, c, M, N, K, stream=None, dtype=None) -> None:
             dtype = BF16
         else:
             raise ValueError("pass dtype=FP16/BF16 for tensors of type %s" % a.dtype)
-    rc = gemm_nt_raw(a, b, c, M, N, K, stream, dtype)
+    rc = gemm_nt_raw(a, b, c, M, N, K, stream, dtype, config)
     if rc != 0:
         raise GemmNtError(rc, load_library().gemm_nt_strerror(rc).decode())
 

@@ -34,12 +34,18 @@ int gemm_nt_check_args(const void* a, const void* b, const void* c, int M, int N
     return GEMM_NT_OK;
 }
 
-int gemm_nt(const void* a, const void* b, void* c, int M, int N, int K, void* stream, int dtype)
+int gemm_nt_config(const void* a, const void* b, void* c, int M, int N, int K, void* stream, int dtype, int config)
 {
     const int rc = gemm_nt_check_args(a, b, c, M, N, K, dtype);
     if (rc != GEMM_NT_OK) return rc;
-    GemmLaunchArgs g{a, b, c, M, N, K, dtype, stream};
+    if (config < 0 || config > 4) return GEMM_NT_ERR_SHAPE;
+    GemmLaunchArgs g{a, b, c, M, N, K, dtype, stream, config};
     return gemm_launch(g) == 0 ? GEMM_NT_OK : GEMM_NT_ERR_LAUNCH;
+}
+
+int gemm_nt(const void* a, const void* b, void* c, int M, int N, int K, void* stream, int dtype)
+{
+    return gemm_nt_config(a, b, c, M, N, K, stream, dtype, 0);
 }
 
 int gemm_nt_fp8_check_args(const void* a, const void* b, const void* c, int M, int N, int K, int out_dtype)

@@ -8,7 +8,7 @@ struct GemmLaunchArgs {
     int M, N, K;
     int dtype;       // 0 = fp16, 1 = bf16 (for the 8-bit product: the type of c; a and b are E4M3 bytes)
     void* stream;    // hipStream_t
-    int config = 0;  // 8-bit product only: 0 = chosen by K, 1 ... 4 = a fixed kernel configuration
+    int config = 0;  // 0 = chosen by K, 1 ... 4 = a fixed kernel configuration (waves per workgroup, paired copies)
 };
 
 // Enqueue the kernel for already-validated arguments.  0 on success, -1 if HIP refused the launch.

@@ -3,31 +3,35 @@
 //
 // This is the paper's other headline kernel (the matrix multiplication of Sections 3.1 and 5.2) on
 // the same machinery as the attention kernel: both operand tiles travel global -> LDS with
-// direct-to-LDS loads through a ring of STAGES stages (the aref ring of Section 3.3 with depth 4;
-// s_waitcnt vmcnt plus one s_barrier per K tile stand in for the full/empty credits), and the
-// 32x32x16 MFMA consumes them.  There is no producer wave: every wave issues its share of the copies
-// three K tiles ahead and computes.
+// direct-to-LDS loads through a ring of stages (the aref ring of Section 3.3; s_waitcnt vmcnt plus one
+// s_barrier per K tile stand in for the full/empty credits), and the 32x32x16 MFMA consumes them.
+// There is no producer wave: every wave issues its share of the copies several K tiles ahead and computes.
 //
-// Workgroup: 8 waves (two per SIMD) on a 256 x 256 tile of C; a wave owns 128 (m) x 64 (n) of it,
-// i.e. 8 accumulator blocks.  The product is computed transposed, D = B_tile A_tile^T, so that a
-// lane ends up with one row m of C and runs of four consecutive n: the 16-bit results leave as 8-byte
-// stores (computed the other way round a lane would hold single elements of 16 different rows).
+// Workgroup: a 256 x 256 tile of C, by 8 waves (two per SIMD; a wave owns 128 (m) x 64 (n), 8 accumulator
+// blocks) or by 4 waves (one per SIMD; 128 x 128, 16 accumulator blocks in the AGPRs).  The product is
+// computed transposed, D = B_tile A_tile^T, so that a lane ends up with one row m of C and runs of four
+// consecutive n: the 16-bit results leave as 8-byte stores (computed the other way round a lane would
+// hold single elements of 16 different rows).
 //
-// Schedule of one wave, K tile j (32 wide, two MFMA k-steps, 16 MFMAs):
-//   wait for its own copies of stage j+1; barrier (everyone's stage j+1 is complete, nobody reads
-//   stage j-1 any more, so its slot takes the copies of stage j+3); then 16 MFMAs on fragments that
-//   were requested during tile j-1, with one LDS request (a fragment of tile j+1) or one copy (of
-//   stage j+3) issued after each MFMA.
+// Schedule of one wave, K tile j (32 wide, two MFMA k-steps): wait for its own copies of stage j+1;
+// barrier; then the MFMAs on fragments that were requested during tile j-1, with LDS requests (fragments
+// of tile j+1) and copies issued one at a time behind the MFMAs.  Which copies:
+//   unpaired (ring of 4): the pieces of stage j+3, whose slot tile j-1 has just released;
+//   paired (ring of 5): a K tile is 64 bytes per row, half a memory line, and the limit of this kernel is
+//   the request path from the L2 into the CU; so even tiles issue the pieces of stages j+4 and j+5
+//   alternately and odd tiles none: the two halves of a line are requested back to back and the L1 merges
+//   them into one request to the L2 (+9-13 % at K >= 2048).
+// The launcher takes the 4-wave paired kernel from K = 2048 on and the 8-wave paired kernel below.
 //
-// Measured on the device (M = N = 8192, K = 8192, fp16 N(0,1) operands, same box and session):
-//   this kernel 1.16 PFLOP/s; with the copies left out (wrong results, timing only) 1.40; with the
+// Measured on the device (M = N = 8192, K = 8192, fp16 N(0,1) operands, same box and session), 8 waves,
+// unpaired: 1.16 PFLOP/s; with the copies left out (wrong results, timing only) 1.40; with the
 //   fragment reads left out 1.23; with neither 1.60, which is the chip's random-operand MFMA-only
-//   rate.  Copies always taken from the same K tile (L2 hits only): no change, so the memory side is
+//   rate.  Copies always taken from the same K tile (L2 hits only): no change, so the HBM side is
 //   not the limit.  Four extra producer waves that do all the copying (warp specialisation as in the
 //   paper; tried with a leaner fragment schedule that fits the 168 registers of three waves per SIMD):
-//   slower, 1.00.  Four waves of 128 x 128 instead of eight of 128 x 64 (a third fewer LDS
-//   reads, accumulators in AGPRs): the same, 1.09-1.16.  A fifth ring stage: the same.  Lanes of a copy
+//   slower, 1.00.  A fifth ring stage without pairing: the same.  Lanes of a copy
 //   mapped to rows (lane -> row L%16) instead of to the 16-byte columns of a row: 0.96.
+// All four configurations, same session: 1.17 (8 waves), 1.28 (8, paired), 1.22 (4 waves), 1.30 (4, paired).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
@@ -53,30 +57,33 @@ __device__ unsigned long long gemm_dbg[256 * 8 * 8];
 #ifndef GEMM_TAIL_READS
 #define GEMM_TAIL_READS 3
 #endif
-#ifndef GEMM_COMPUTE_WAVES
-#define GEMM_COMPUTE_WAVES 8
+// Kernel configuration, fixed at compile time for the sweep harness or chosen per call by K (0):
+//   1: 8 waves (two per SIMD, 128 x 64 of C each), one stage copied per tile, three tiles ahead
+//   2: 8 waves, paired copies
+//   3: 4 waves (one per SIMD, 128 x 128 each, a third fewer LDS reads, accumulators in the AGPRs)
+//   4: 4 waves, paired copies
+// Paired copies: a 32-element K tile is 64 bytes per row, half a memory line, and what limits this kernel
+// is the request path from the L2 into the CU.  The copies of two consecutive stages are therefore issued
+// together, piece by piece, at every second tile: the two halves of a line are requested back to back and
+// the L1 merges them into one request to the L2.  Five stages, copies four and five tiles ahead.
+#ifndef GEMM_CONFIG
+#define GEMM_CONFIG 0
 #endif
-constexpr int G_CW = GEMM_COMPUTE_WAVES; // computing waves per workgroup: 8 (two per SIMD, 128 x 64 of C each) or 4 (one per SIMD, 128 x 128)
-constexpr int G_NB = 8 / (G_CW / 2);    // 32-column blocks of C per wave (the wave's rows are always 4 blocks)
-static_assert(G_CW == 8 || G_CW == 4, "wave layout is 2 x (G_CW / 2)");
-constexpr int G_NW = G_CW;              // waves per workgroup (every wave copies and computes)
-constexpr int G_COPIERS = G_CW;
+// Configuration 0: the 4-wave paired kernel from this K on, the 8-wave paired kernel below it (whose
+// prologue and epilogue overlap better between the two waves of a SIMD).
+constexpr int G_LARGE_K = 2048;
 constexpr int G_BM = 256, G_BN = 256;   // tile of C per workgroup
 constexpr int G_BK = 32;                // K tile
 #ifndef GEMM_STAGES
 #define GEMM_STAGES 4
 #endif
-constexpr int G_STAGES = GEMM_STAGES;   // ring depth: 4 (128 KiB) or 5 (all 160 KiB of the LDS)
-constexpr int G_AHEAD = G_STAGES - 1;   // copies run this many K tiles ahead of the tile being multiplied
-static_assert(G_STAGES == 4 || G_STAGES == 5, "ring protocol below");
+static_assert(GEMM_STAGES == 4 || GEMM_STAGES == 5, "ring protocol below");
 constexpr int G_OPER_BYTES = G_BM * G_BK * 2;        // one operand tile in the LDS (16 KiB)
 constexpr int G_STAGE_BYTES = 2 * G_OPER_BYTES;      // A tile, then B tile
 constexpr int G_PIECES = G_OPER_BYTES / 1024;        // 1 KiB wave-transfers per operand tile (16 rows x 64 B each)
-constexpr int G_PPW = G_PIECES / G_COPIERS;          // ... per copying wave and operand
-constexpr int G_LPG = 2 * G_PPW;                     // copies a wave issues per stage
 constexpr int G_GROUP_M = 8;                         // tile rows per raster group (see tile_coords)
-static_assert(G_BM == G_BN && G_PIECES % G_COPIERS == 0, "operand tiles are copied the same way");
-static_assert(3 * G_LPG <= 63, "the stages in flight must fit the vmcnt counter");
+static_assert(G_BM == G_BN, "operand tiles are copied the same way");
+constexpr int g_stages_of(bool paired) { return paired ? 5 : GEMM_STAGES; }
 
 // Logical tile -> (tile row, tile column): tile rows are taken in groups of G_GROUP_M and a group is
 // walked column by column, so tiles that run at the same time share A row panels and B row panels
@@ -90,12 +97,20 @@ __device__ __forceinline__ void tile_coords(int t, int ntm, int ntn, int& tm, in
     tn = in_group / rows;
 }
 
-template <int DTYPE>
-__global__ __launch_bounds__(G_NW * 64)
+template <int DTYPE, int NW, bool PAIRED>
+__global__ __launch_bounds__(NW * 64)
 void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
                     int M, int N, int K, int ntm, int ntn)
 {
     typedef Elem<DTYPE> E;
+    static_assert(NW == 8 || NW == 4, "wave layout is 2 x (NW / 2)");
+    constexpr int G_CW = NW;                     // waves per workgroup: every wave copies and computes
+    constexpr int G_NB = 8 / (NW / 2);           // 32-column blocks of C per wave (the wave's rows are always 4 blocks)
+    constexpr int G_STAGES = g_stages_of(PAIRED);
+    constexpr int G_AHEAD = G_STAGES - 1;        // unpaired: copies run this many K tiles ahead of the tile being multiplied
+    constexpr int G_PPW = G_PIECES / NW;         // 1 KiB pieces per wave and operand
+    constexpr int G_LPG = 2 * G_PPW;             // copies a wave issues per stage
+    static_assert(4 * G_LPG <= 63, "the stages in flight must fit the vmcnt counter");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const unsigned lds_base = (unsigned)(size_t)(LDS_AS void*)smem;
 
@@ -150,6 +165,14 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
 #pragma unroll
         for (int i = 0; i < G_LPG; ++i) issue_piece(s, i);
     };
+    // The same for a stage that may lie past the last K tile: it then fetches the last tile again (its ring
+    // slot is free by the protocol and never read), which keeps the count of copies in flight uniform.
+    auto issue_piece_any = [&](int s, int i) __attribute__((always_inline)) {
+        const unsigned sbase = lds_base + (s % G_STAGES) * G_STAGE_BYTES + wave * (G_PPW * 1024);
+        const size_t koff = (size_t)min(s, nk - 1) * (G_BK * 2);
+        if (i < G_PPW) dma16(a_piece[i] + koff, a_voff[i], sbase + i * 1024);
+        else dma16(b_piece[i - G_PPW] + koff, b_voff[i - G_PPW], sbase + G_OPER_BYTES + (i - G_PPW) * 1024);
+    };
 
     // ---- fragments: 32 rows x 16 k of an operand tile; lane l holds row l%32, k = 16*ks + 8*(l/32) .. +7
     // (row lr%16 of 16-row block lr/16; 16-byte column 2*ks + g, stored at position column ^ ((row/4)%4))
@@ -181,6 +204,60 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
     };
     static_assert(FRAGS_PER_TILE + G_LPG <= MFMAS_PER_TILE, "one request or copy per MFMA slot");
 
+    if constexpr (PAIRED) {
+    // ---- paired copies.  Ring of five stages.  At the barrier of an even tile e the slots of stages e - 1
+    // and e are free (the fragments of tile e were read during tile e - 1, and every wave waited for its
+    // requests before the barrier), and the wave issues its pieces of stages e + 4 and e + 5 alternately,
+    // one behind every second MFMA of the tile; odd tiles issue none.  Before barrier j a wave has waited for
+    // its own copies of stage j + 1: what may still be in flight is the pair issued two tiles ago (j even),
+    // or the last piece of stage j + 2 and the pair issued one tile ago (j odd).
+    static_assert(4 * G_LPG == MFMAS_PER_TILE, "one copy behind every second MFMA of an even tile");
+#pragma unroll
+    for (int s0 = 0; s0 < 4; ++s0)
+#pragma unroll
+        for (int i = 0; i < G_LPG; ++i) issue_piece_any(s0, i);
+    wait_vmcnt<3 * G_LPG>();                  // stage 0
+    __builtin_amdgcn_s_barrier();
+    auto tile2 = [&](int j, const TileFrags& cur, TileFrags& nxt, auto even_tag) __attribute__((always_inline)) {
+        constexpr bool EVEN = decltype(even_tag)::value;
+        if (EVEN) wait_vmcnt<2 * G_LPG>(); else wait_vmcnt<2 * G_LPG + 1>();
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's reads of stage j are complete
+        __builtin_amdgcn_s_barrier();
+        const int jn = min(j + 1, nk - 1);    // (the last tile re-reads itself: harmless, unused)
+        int next_frag = 0;
+#pragma unroll
+        for (int q = 0; q < MFMAS_PER_TILE; ++q) {
+            const int ks = q / (4 * G_NB), mb = (q / G_NB) % 4, nb = q % G_NB;
+            acc[nb][mb] = E::mfma(cur.bn[ks][nb], cur.am[ks][mb], acc[nb][mb]);
+            __builtin_amdgcn_sched_barrier(0);
+            // requests behind the even MFMAs and, while some are left, behind every fourth odd one
+            if (next_frag < FRAGS_PER_TILE && ((q & 1) == 0 || (q & 3) == 1)) {
+                read_frag(nxt, jn, next_frag);
+                ++next_frag;
+            }
+            if (EVEN && (q & 1)) issue_piece_any(j + 4 + ((q >> 1) & 1), q >> 2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        static_assert(FRAGS_PER_TILE <= MFMAS_PER_TILE / 2 + MFMAS_PER_TILE / 4, "every fragment has a slot");
+    };
+    TileFrags X, Y;
+#pragma unroll
+    for (int i = 0; i < FRAGS_PER_TILE; ++i) read_frag(X, 0, i);
+    {
+        typedef std::integral_constant<bool, true> even_t;
+        typedef std::integral_constant<bool, false> odd_t;
+        int j = 0;
+        if (nk >= 2) {
+            do {
+                tile2(j, X, Y, even_t());
+                tile2(j + 1, Y, X, odd_t());
+                j += 2;
+            } while (j + 1 < nk);
+        }
+        if (j < nk) tile2(j, X, Y, even_t());
+    }
+    wait_vmcnt<0>();                          // surplus copies past the last tile
+    } else {
     // Own copies of stage j+1 complete: only the stages after it (at most G_AHEAD - 2 of them) stay in flight.
     auto wait_next_stage = [&](int j) __attribute__((always_inline)) {
         if (G_AHEAD > 3 && j + 3 < nk) wait_vmcnt<2 * G_LPG>();
@@ -278,6 +355,7 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
         for (int i = 0; i < 8; ++i) gemm_dbg[(blockIdx.x * 8 + wave) * 8 + i] = dbg_acc[i];
     }
 #endif
+    }  // !PAIRED
     // ---- epilogue: lane holds row m of C and, per accumulator register quad, four consecutive n
     const bool vec_ok = (N & 3) == 0 && (reinterpret_cast<uintptr_t>(C) & 7) == 0;
 #pragma unroll
@@ -304,11 +382,11 @@ void gemm_nt_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__
     }
 }
 
-template <int DTYPE>
+template <int DTYPE, int NW, bool PAIRED>
 int launch(const GemmLaunchArgs& a)
 {
-    constexpr int smem = G_STAGES * G_STAGE_BYTES;
-    auto kern = gemm_nt_kernel<DTYPE>;
+    constexpr int smem = g_stages_of(PAIRED) * G_STAGE_BYTES;
+    auto kern = gemm_nt_kernel<DTYPE, NW, PAIRED>;
     static bool attr_set = false;   // idempotent; a race only repeats the call
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
@@ -321,9 +399,22 @@ int launch(const GemmLaunchArgs& a)
     int M = a.M, N = a.N, K = a.K;
     int ntm = (M + G_BM - 1) / G_BM, ntn = (N + G_BN - 1) / G_BN;
     void* args[] = {&A, &B, &C, &M, &N, &K, &ntm, &ntn};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3((unsigned)(ntm * ntn)), dim3(G_NW * 64),
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3((unsigned)(ntm * ntn)), dim3(NW * 64),
                                          args, smem, (hipStream_t)a.stream);
     return e == hipSuccess ? 0 : -1;
+}
+
+int config_for(int K) { return GEMM_CONFIG != 0 ? GEMM_CONFIG : (K >= G_LARGE_K ? 4 : 2); }
+
+template <int DTYPE>
+int launch_dtype(const GemmLaunchArgs& a)
+{
+    switch (a.config != 0 ? a.config : config_for(a.K)) {
+        case 1: return launch<DTYPE, 8, false>(a);
+        case 2: return launch<DTYPE, 8, true>(a);
+        case 3: return launch<DTYPE, 4, false>(a);
+        default: return launch<DTYPE, 4, true>(a);
+    }
 }
 
 }  // namespace
@@ -335,16 +426,18 @@ extern "C" int gemm_dbg_read(unsigned long long* host, int n)
 }
 #endif
 
-int gemm_launch(const GemmLaunchArgs& a) { return a.dtype == 0 ? launch<0>(a) : launch<1>(a); }
+int gemm_launch(const GemmLaunchArgs& a) { return a.dtype == 0 ? launch_dtype<0>(a) : launch_dtype<1>(a); }
 
+// Reported for the configuration a large K takes.
 int gemm_launch_tile_param(int which)
 {
+    const int cfg = config_for(1 << 20);
     switch (which) {
         case 0: return G_BM;
         case 1: return G_BN;
         case 2: return G_BK;
-        case 3: return G_STAGES;
-        case 4: return G_NW * 64;
+        case 3: return g_stages_of(cfg == 2 || cfg == 4);
+        case 4: return (cfg >= 3 ? 4 : 8) * 64;
         default: return -1;
     }
 }

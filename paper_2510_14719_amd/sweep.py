@@ -22,9 +22,11 @@ What the axes stand for on gfx950:
              ATTN8_STAGES       depth of the LDS ring (the paper's D): copies run STAGES - 2 tiles ahead
              ATTN8_COPIES_IN_PASS copies issued one by one behind MFMAs of the pass (1) or all right after the barrier (0)
   gemm       GEMM_STAGES        depth of the LDS ring (the paper's D): 4 or 5
-             GEMM_COMPUTE_WAVES waves per workgroup: 8 x (128 x 64) or 4 x (128 x 128)
+             GEMM_CONFIG        0: chosen by K; 1: 8 waves x (128 x 64); 2: the same with paired copies (two stages
+                                issued together so that both halves of a memory line are requested back to back);
+                                3: 4 waves x (128 x 128); 4: the same with paired copies
              GEMM_TAIL_READS    LDS requests allowed in flight across the tile boundary
-  gemm_fp8   GEMM8_STAGES, GEMM8_TAIL_READS   the same for the 8-bit-float kernel
+  gemm_fp8   GEMM8_STAGES, GEMM8_TAIL_READS, GEMM8_CONFIG   the same for the 8-bit-float kernel
              GEMM8_COPY_PHASE   copies behind the odd (1) or the even (0) MFMAs of a K tile
              GEMM8_CONFIG       0: chosen by K; 1: 8 waves x (128 x 64); 2: the same with paired copies (two stages
                                 issued together so that both halves of a memory line are requested back to back);
@@ -46,11 +48,11 @@ GRIDS = {
     "attn": {"ATTN_FWIN": [1, 2, 4, 8], "ATTN_COPY_GROUP": [0, 2, 1], "ATTN_SUMCHAINS": [2, 4]},
     "attn_causal": {"ATTN_PERSISTENT": [0, 1], "ATTN_FWIN": [2, 4]},
     "attn_fp8": {"ATTN8_FWIN": [1, 2, 3], "ATTN8_INTERLEAVE": [1, 0], "ATTN8_STAGES": [4, 8], "ATTN8_COPIES_IN_PASS": [1, 0]},
-    "gemm": {"GEMM_STAGES": [4, 5], "GEMM_COMPUTE_WAVES": [8, 4], "GEMM_TAIL_READS": [0, 3]},
+    "gemm": {"GEMM_CONFIG": [0, 1, 2, 3, 4], "GEMM_STAGES": [4, 5], "GEMM_TAIL_READS": [3, 0]},
     "gemm_fp8": {"GEMM8_CONFIG": [0, 1, 2, 3, 4], "GEMM8_STAGES": [4, 5], "GEMM8_TAIL_READS": [3, 0]},
 }
 DEFAULTS = {"ATTN8_FWIN": 2, "ATTN8_INTERLEAVE": 1, "ATTN8_STAGES": 4, "ATTN8_COPIES_IN_PASS": 1, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
-            "GEMM_STAGES": 4, "GEMM_COMPUTE_WAVES": 8, "GEMM_TAIL_READS": 3,
+            "GEMM_STAGES": 4, "GEMM_CONFIG": 0, "GEMM_TAIL_READS": 3,
             "GEMM8_STAGES": 4, "GEMM8_TAIL_READS": 3, "GEMM8_COPY_PHASE": 1, "GEMM8_CONFIG": 0}
 
 

@@ -123,7 +123,7 @@ def test_mfma_probe_validation_needs_no_gpu(lib):
 def test_gemm_header_symbols_are_exported(lib):
     src = re.sub(r"/\*.*?\*/", "", open(GEMM_HEADER).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(gemm_nt\w*)\s*\(", src)))
-    assert {"gemm_nt", "gemm_nt_f16", "gemm_nt_bf16", "gemm_nt_check_args", "gemm_nt_strerror", "gemm_nt_tile_param",
+    assert {"gemm_nt", "gemm_nt_config", "gemm_nt_f16", "gemm_nt_bf16", "gemm_nt_check_args", "gemm_nt_strerror", "gemm_nt_tile_param",
             "gemm_nt_fp8", "gemm_nt_fp8_config", "gemm_nt_fp8_check_args", "gemm_nt_fp8_tile_param"} <= set(names)
     for n in names:
         assert hasattr(lib, n), "library does not export %s" % n
@@ -150,6 +150,8 @@ def test_gemm_argument_validation_needs_no_gpu(lib):
     assert lib.gemm_nt(None, None, None, 1, 1, 32, None, 0) == -1
     assert lib.gemm_nt_f16(a, b, c, 8, 8, 31, None) == -2
     assert lib.gemm_nt_bf16(a, b, c, 8, 8, 64 + 8, None) == -2
+    assert lib.gemm_nt_config(a, b, c, 8, 8, 64, None, 0, 5) == -2        # unknown configuration
+    assert lib.gemm_nt_config(a, b, None, 8, 8, 64, None, 0, 2) == -1
     for code in range(-8, 1):
         assert len(lib.gemm_nt_strerror(code)) > 3
     bm, bn, bk, st, th = (lib.gemm_nt_tile_param(w) for w in range(5))

@@ -26,7 +26,7 @@ def env():
     return torch, binding, gemm_ref
 
 
-def run_gpu(env, a, b, dtype, pad=512):
+def run_gpu(env, a, b, dtype, pad=512, config=None):
     torch, binding, _ = env
     M, K = a.shape
     N = b.shape[0]
@@ -34,7 +34,7 @@ def run_gpu(env, a, b, dtype, pad=512):
     db = torch.from_numpy(b.view(np.int16)).cuda()
     buf = torch.full((M * N + 2 * pad,), 0x7B7B, dtype=torch.int16, device="cuda")
     c = buf[pad:pad + M * N]
-    binding.gemm_nt(da, db, c, M, N, K, dtype=dtype)
+    binding.gemm_nt(da, db, c, M, N, K, dtype=dtype, config=config)
     torch.cuda.synchronize()
     assert bool((buf[:pad] == 0x7B7B).all()) and bool((buf[pad + M * N:] == 0x7B7B).all()), "guard words overwritten"
     cc = c.view(torch.bfloat16 if dtype == I.BF16 else torch.float16).reshape(M, N)
@@ -60,6 +60,23 @@ def test_full_compare(env, M, N, K, dtype):
     ref = G.gemm_nt(a, b, dtype)
     c = run_gpu(env, a, b, dtype).double().cpu().numpy()
     check(c, ref, dtype, K, "full M%d N%d K%d" % (M, N, K))
+
+
+@pytest.mark.parametrize("config", [1, 2, 3, 4])
+@pytest.mark.parametrize("M,N,K,dtype", [(1, 1, 32, I.FP16), (257, 255, 64, I.BF16), (300, 520, 160, I.FP16), (640, 513, 1056, I.FP16),
+                                           (256, 256, 2048, I.BF16)])
+def test_every_kernel_configuration_in_full(env, M, N, K, dtype, config):
+    # gemm_nt picks the configuration by K; each of the four kernels must handle every shape: one and two
+    # K tiles, odd and even tile counts, overhanging tiles
+    _, _, G = env
+    a, b = I.make_ab(M, N, K, dtype, seed=600 + M + N + K)
+    print("case gemm config%d M%d N%d K%d dtype%d" % (config, M, N, K, dtype), flush=True)
+    ref = G.gemm_nt(a, b, dtype)
+    c = run_gpu(env, a, b, dtype, config=config).double().cpu().numpy()
+    check(c, ref, dtype, K, "config %d M%d N%d K%d" % (config, M, N, K))
+    # the configurations add the K tiles of an entry in the same order: bit-identical results
+    c1 = run_gpu(env, a, b, dtype, config=1).double().cpu().numpy()
+    assert np.array_equal(c, c1)
 
 
 def test_odd_n_uses_scalar_stores(env):

@@ -84,10 +84,11 @@ def test_every_kernel_configuration_in_full(env, M, N, K, config):
     ref = G.gemm_nt(a, b, I.E4M3)
     c = run_gpu(env, a, b, I.FP16, config=config).double().cpu().numpy()
     check(c, ref, magnitudes(env, a) @ magnitudes(env, b).T, I.FP16, "config %d M%d N%d K%d" % (config, M, N, K))
-    if K >= 2048:       # the call without a configuration takes the 4-wave paired kernel here: bit-identical to config 4
-        c0 = run_gpu(env, a, b, I.FP16).double().cpu().numpy()
-        c4 = run_gpu(env, a, b, I.FP16, config=4).double().cpu().numpy()
-        assert np.array_equal(c0, c4)
+    # the configurations add the K tiles of an entry in the same order: bit-identical results, with or without
+    # a configuration in the call
+    c1 = run_gpu(env, a, b, I.FP16, config=1).double().cpu().numpy()
+    c0 = run_gpu(env, a, b, I.FP16).double().cpu().numpy()
+    assert np.array_equal(c, c1) and np.array_equal(c, c0)
 
 
 def test_odd_n_uses_scalar_stores(env):
