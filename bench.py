@@ -33,8 +33,8 @@ DTYPE_NAME = {0: "fp16", 1: "bf16", 2: "fp8-e4m3"}
 # what the counter reads for a 1 GiB copy); a profile's figure, not measured by this script.
 MEASURED_TRAFFIC = {"c4": ((163994.6 * 2.000 + 67133.9 * 1.000) * 1024.0, "profiles/attn_fwd_c4_fp16_noncausal.md"),
                     "f4": ((89711.5 * 2.000 + 105472.0 * 1.000) * 1024.0, "profiles/attn_fwd_fp8_f4_e4m3_noncausal.md"),
-                    ("gemm", 16384): ((3267434.0 * 2.000 + 138227.0 * 1.000) * 1024.0, "profiles/gemm_nt_m8192_n8192_k16384_fp16.md"),
-                    ("gemm_fp8", 16384): ((801891.4 * 2.000 + 138042.0 * 1.000) * 1024.0, "profiles/gemm_nt_fp8_m8192_n8192_k16384_e4m3.md")}
+                    ("gemm", 16384): ((1657777.6 * 2.000 + 143495.7 * 1.000) * 1024.0, "profiles/gemm_nt_m8192_n8192_k16384_fp16.md"),
+                    ("gemm_fp8", 16384): ((787342.1 * 2.000 + 152647.8 * 1.000) * 1024.0, "profiles/gemm_nt_fp8_m8192_n8192_k16384_e4m3.md")}
 
 
 def describe(w) -> str:
