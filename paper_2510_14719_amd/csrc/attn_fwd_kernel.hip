@@ -66,6 +66,13 @@ constexpr float RESCALE_LOG2 = 8.0f;
 #define ATTN_COPY_GROUP 0
 #endif
 
+// 1: in the steady state a wave issues its copies of a stage one at a time between the exponentials of the
+// softmax; 0: as one block before the softmax (a wave is held ~270 cycles per tile by that block).  Measured
+// on MI355X: spreading them loses 1-2 % (c3, c4, c5), so the block stays.
+#ifndef ATTN_COPIES_IN_SOFTMAX
+#define ATTN_COPIES_IN_SOFTMAX 0
+#endif
+
 #ifdef ATTN_TIMING
 // Profiling builds only: per-wave cycle totals of the main-loop sections of the first workgroups.
 constexpr int DBG_WGS = 1024, DBG_SLOTS = ATTN_TIMING >= 3 ? 32 : 8;
@@ -221,6 +228,13 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         }
     };
 
+    // One copy of a stage that lies wholly inside the sequence: K piece i < CPW, else V piece i - CPW.
+    auto issue_piece_inside = [&](int s, int i) __attribute__((always_inline)) {
+        const unsigned sbase = lds_base + ((s + STAGES) % STAGES) * STAGE_BYTES;
+        if (i < CPW) dma16(kh + (size_t)(s + 1) * TILE_BYTES + piece_src[i], k_lane_off, sbase + piece_dst[i]);
+        else dma16(vh + (size_t)s * TILE_BYTES + piece_src[i - CPW], v_lane_off, sbase + TILE_BYTES + piece_dst[i - CPW]);
+    };
+
     // ---- prologue of a tile: three stages in flight, Q fragments into registers
     s16x8 Qf[MB][KK];
     auto prologue = [&]() __attribute__((always_inline)) {
@@ -306,7 +320,12 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // Base-2 exponentials with the scale folded into the exponent.  The running reference m only
     // moves when a row maximum grew by more than 2^RESCALE_LOG2 (the probabilities then stay below
     // that factor), so the rescaling of O is rare after the first tiles.
-    auto softmax_tile = [&](int j) __attribute__((always_inline)) {
+    // With `spread` the wave's copies of stage j + 2 (known to lie inside the sequence) go out between the
+    // exponentials, evenly spaced.
+    auto softmax_tile = [&](int j, auto spread) __attribute__((always_inline)) {
+        constexpr bool SPREAD = decltype(spread)::value;
+        constexpr int NPAIR = KB * 8, NCOPY = 2 * CPW, PER = NPAIR / NCOPY;
+        static_assert(!SPREAD || (PER >= 1 && PER * NCOPY == NPAIR), "copies spread evenly over the exponentials");
         const int kv0 = j * BN;
         if ((kv0 + BN > N) || (CAUSAL && kv0 + BN - 1 > wq0)) {
 #pragma unroll
@@ -354,6 +373,11 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                     const unsigned w = E::pack2(p0, p1);
                     pw[mb][kb * 8 + t] = w;
                     sum[t % NCH] = E::add_pair(w, sum[t % NCH]);
+                    if (SPREAD && mb == 0 && (kb * 8 + t) % PER == PER / 2) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (copies) issue_piece_inside(j + 2, (kb * 8 + t) / PER);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             float tile_sum = sum[0];
 #pragma unroll
@@ -458,16 +482,16 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         wait_stage(0);
         mfma_burst(std::false_type{}, std::true_type{}, stage_ptr(-1));                  // T_0
         if (2 < nt) issue_stage(2);
-        softmax_tile(0);
-        auto iter_a = [&](int j) __attribute__((always_inline)) {
+        softmax_tile(0, std::false_type{});
+        auto iter_a = [&](int j, auto spread) __attribute__((always_inline)) {
             TSTAMP(t0);
             wait_stage(j);
             TSTAMP(t1);
             mfma_burst(std::true_type{}, std::true_type{}, stage_ptr(j - 1));
             TSTAMP(t2);
-            if (j + 2 < nt) issue_stage(j + 2);
+            if (!decltype(spread)::value && j + 2 < nt) issue_stage(j + 2);
             TSTAMP(t3);
-            softmax_tile(j);
+            softmax_tile(j, spread);
             TSTAMP(t4);
             TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3); TACC(3, t3, t4);
         };
@@ -475,9 +499,16 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         // value is also live on the exit edge, the first MFMA of an iteration then cannot update it
         // in place, and the compiler copies all 64 accumulator registers back every iteration)
         int j = 1;
+        // iterations whose stage j + 2 exists and lies wholly inside the sequence spread its copies
+        const int j_spread = ATTN_COPIES_IN_SOFTMAX ? min(nt_w, min(nt - 2, N / BN - 3)) : 0;
+        if (j < j_spread) {
+            do {
+                iter_a(j, std::true_type{});
+            } while (++j < j_spread);
+        }
         if (j < nt_w) {
             do {
-                iter_a(j);
+                iter_a(j, std::false_type{});
             } while (++j < nt_w);
         }
         if (j < nt) wait_stage(j);                                                       // j == nt_w
@@ -491,27 +522,33 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     } else {
         // group B, iteration j: C_j then [U_j, T_{j+1}]; both contractions read stage j
         mfma_burst(std::false_type{}, std::true_type{}, stage_ptr(-1));                  // T_0
-        auto iter_b = [&](int j) __attribute__((always_inline)) {
+        auto iter_b = [&](int j, auto spread) __attribute__((always_inline)) {
             TSTAMP(t0);
             wait_stage(j);
             TSTAMP(t1);
-            if (j + 2 < nt) issue_stage(j + 2);
+            if (!decltype(spread)::value && j + 2 < nt) issue_stage(j + 2);
             TSTAMP(t2);
-            softmax_tile(j);
+            softmax_tile(j, spread);
             TSTAMP(t3);
             mfma_burst(std::true_type{}, std::true_type{}, stage_ptr(j));
             TSTAMP(t4);
             TACC(0, t0, t1); TACC(2, t1, t2); TACC(3, t2, t3); TACC(1, t3, t4);
         };
         int j = 0;
+        const int j_spread = ATTN_COPIES_IN_SOFTMAX ? min(nt_w - 1, min(nt - 2, N / BN - 3)) : 0;
+        if (j < j_spread) {
+            do {
+                iter_b(j, std::true_type{});
+            } while (++j < j_spread);
+        }
         if (j + 1 < nt_w) {
             do {
-                iter_b(j);
+                iter_b(j, std::false_type{});
             } while (++j + 1 < nt_w);
         }
         wait_stage(j);                                                                   // j == nt_w - 1
         if (j + 2 < nt) issue_stage(j + 2);
-        softmax_tile(j);
+        softmax_tile(j, std::false_type{});
         mfma_burst(std::true_type{}, std::false_type{}, stage_ptr(j));                   // U of the last tile
         for (++j; j < nt; ++j) {                                                         // idle tail of a causal wave
             wait_stage(j);
