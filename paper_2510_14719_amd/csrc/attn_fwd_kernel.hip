@@ -68,7 +68,8 @@ constexpr float RESCALE_LOG2 = 8.0f;
 
 // 1: in the steady state a wave issues its copies of a stage one at a time between the exponentials of the
 // softmax; 0: as one block before the softmax (a wave is held ~270 cycles per tile by that block).  Measured
-// on MI355X: spreading them loses 1-2 % (c3, c4, c5), so the block stays.
+// on MI355X: spreading them loses 1-2 % (c3, c4, c5), and so does issuing the block at a different point
+// of the softmax in each wave of a group: the ~70 cycles per copy instruction are not a queue, so the block stays.
 #ifndef ATTN_COPIES_IN_SOFTMAX
 #define ATTN_COPIES_IN_SOFTMAX 0
 #endif
