@@ -52,7 +52,7 @@ enum {
     ATTN_FWD_ERR_ALIGN = -4,      /* a pointer is not 16-byte aligned */
     ATTN_FWD_ERR_OVERFLOW = -5,   /* B*H*N*d does not fit the kernel's 32-bit element indexing */
     ATTN_FWD_ERR_LAUNCH = -6,     /* the HIP runtime refused the launch */
-    ATTN_FWD_ERR_ALIAS = -7       /* o overlaps q, k or v */
+    ATTN_FWD_ERR_ALIAS = -7       /* o or lse overlaps q, k, v or each other */
 };
 
 enum { ATTN_FWD_FP16 = 0, ATTN_FWD_BF16 = 1 };

@@ -3,35 +3,37 @@
 ``python -m paper_2510_14719_amd.build`` compiles every HIP source for gfx950
 (hipcc cross-compiles; no GPU is needed) and links the C-ABI library next to
 this file.  Nothing is built at import time or inside tests.
+
+Every source is compiled to an object of its own (in parallel) under ``_build/``
+and the objects are linked; an object is reused when it is newer than its source
+and every header, and was made with the same flags (``force`` recompiles all).
 """
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libattn_fwd.so")
+OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["attn_fwd_kernel.hip", "attn_fwd_fp8_kernel.hip", "mfma_probe.hip", "attn_api.cpp", "gemm_nt_kernel.hip", "gemm_nt_fp8_kernel.hip", "gemm_api.cpp"]
+SOURCES = ["attn_fwd_kernel.hip", "attn_fwd_pipe_kernel.hip", "attn_fwd_fp8_kernel.hip", "mfma_probe.hip", "attn_api.cpp",
+           "gemm_nt_kernel.hip", "gemm_nt_fp8_kernel.hip", "gemm_api.cpp"]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-fp32 VALU forms are kept out of every kernel of this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 
 
-def build(extra_defines=(), out: str = LIB, verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE, "-I", CSRC]
-    cmd += ["-D%s" % d for d in extra_defines]
-    cmd += ["-x", "hip"] + [os.path.join(CSRC, s) for s in SOURCES]
-    tmp = out + ".tmp.%d" % os.getpid()
-    cmd += ["-o", tmp]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -40,10 +42,35 @@ def build(extra_defines=(), out: str = LIB, verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + log)
     if verbose and log.strip():
         print(log)
+
+
+def build(extra_defines=(), out: str = LIB, verbose: bool = False, force: bool = False, jobs: int = 8) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [*HIPCC_FLAGS, "-I", INCLUDE, "-I", CSRC] + ["-D%s" % d for d in extra_defines]
+    tag = hashlib.sha1(" ".join([hipcc] + flags).encode()).hexdigest()[:12]
+    odir = os.path.join(OBJ_DIR, tag)
+    os.makedirs(odir, exist_ok=True)
+    headers = [os.path.join(d, f) for d in (CSRC, INCLUDE) for f in os.listdir(d) if f.endswith(".h")]
+    newest_header = max(os.path.getmtime(h) for h in headers)
+
+    def compile_one(src):
+        obj = os.path.join(odir, src + ".o")
+        path = os.path.join(CSRC, src)
+        if not force and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(path), newest_header):
+            return obj
+        tmp = obj + ".tmp.%d" % os.getpid()
+        _run([hipcc, *flags, "-x", "hip", "-c", path, "-o", tmp], verbose)
+        os.replace(tmp, obj)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    tmp = out + ".tmp.%d" % os.getpid()
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp], verbose)
     os.replace(tmp, out)
     return out
 
 
 if __name__ == "__main__":
-    build(extra_defines=sys.argv[1:], verbose=True)
+    build(extra_defines=[a for a in sys.argv[1:] if a != "--force"], verbose=True, force="--force" in sys.argv[1:])
     print("built", LIB)

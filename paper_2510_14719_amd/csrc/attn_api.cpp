@@ -39,7 +39,10 @@ int attn_fwd_check_args(const void* q, const void* k, const void* v, const void*
     const unsigned long long tiles = ((unsigned long long)N + bm - 1) / bm * (unsigned long long)B * (unsigned long long)H;
     if (tiles >= (1ull << 31)) return ATTN_FWD_ERR_OVERFLOW;
     const unsigned long long bytes = head_bytes * (unsigned long long)B * (unsigned long long)H;
+    const unsigned long long lse_bytes = 4ull * (unsigned long long)N * (unsigned long long)B * (unsigned long long)H;
     if (overlaps(o, bytes, q, bytes) || overlaps(o, bytes, k, bytes) || overlaps(o, bytes, v, bytes)) return ATTN_FWD_ERR_ALIAS;
+    if (overlaps(lse, lse_bytes, q, bytes) || overlaps(lse, lse_bytes, k, bytes) || overlaps(lse, lse_bytes, v, bytes) ||
+        overlaps(lse, lse_bytes, o, bytes)) return ATTN_FWD_ERR_ALIAS;
     return ATTN_FWD_OK;
 }
 
@@ -82,8 +85,11 @@ int attn_fwd_fp8_check_args(const void* q, const void* k, const void* v, const v
     const unsigned long long tiles = ((unsigned long long)N + bm - 1) / bm * (unsigned long long)B * (unsigned long long)H;
     if (tiles >= (1ull << 31)) return ATTN_FWD_ERR_OVERFLOW;
     const unsigned long long in_bytes = head_elems * (unsigned long long)B * (unsigned long long)H, out_bytes = 2ull * in_bytes;
+    const unsigned long long lse_bytes = 4ull * (unsigned long long)N * (unsigned long long)B * (unsigned long long)H;
     if (overlaps(o, out_bytes, q, in_bytes) || overlaps(o, out_bytes, k, in_bytes) || overlaps(o, out_bytes, v, in_bytes))
         return ATTN_FWD_ERR_ALIAS;
+    if (overlaps(lse, lse_bytes, q, in_bytes) || overlaps(lse, lse_bytes, k, in_bytes) || overlaps(lse, lse_bytes, v, in_bytes) ||
+        overlaps(lse, lse_bytes, o, out_bytes)) return ATTN_FWD_ERR_ALIAS;
     return ATTN_FWD_OK;
 }
 
@@ -108,7 +114,7 @@ const char* attn_fwd_strerror(int code)
         case ATTN_FWD_ERR_ALIGN: return "pointers must be 16-byte aligned";
         case ATTN_FWD_ERR_OVERFLOW: return "problem too large for the kernel's index arithmetic";
         case ATTN_FWD_ERR_LAUNCH: return "HIP refused the kernel launch";
-        case ATTN_FWD_ERR_ALIAS: return "o overlaps q, k or v";
+        case ATTN_FWD_ERR_ALIAS: return "o or lse overlaps an input, or each other";
         default: return "unknown error code";
     }
 }

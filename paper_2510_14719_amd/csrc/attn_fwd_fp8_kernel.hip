@@ -56,6 +56,7 @@
 
 #include "attn_launch.h"
 #include "gfx950_prims.h"
+#include "launch_once.h"
 #include "tile_schedule.h"
 
 namespace {
@@ -559,12 +560,8 @@ int launch_fp8(const AttnLaunchArgs& a)
     constexpr int BM = 256;
     constexpr int smem = ATTN8_STAGES * 2 * BN * D;
     auto kern = attn_fwd_fp8_kernel<OUT, D, BN, CAUSAL>;
-    static bool attr_set = false;   // idempotent; a race only repeats the call
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return -1;
-        attr_set = true;
-    }
+    static PerDeviceOnce once;                  // the attribute belongs to the (kernel, device) pair
+    if (once.prepare(reinterpret_cast<const void*>(kern), smem) < 0) return -1;
     const int nqt = (a.N + BM - 1) / BM;
     const long long total = (long long)nqt * a.B * a.H;
     const float log2e = 1.4426950408889634f;

@@ -35,6 +35,7 @@
 
 #include "attn_launch.h"
 #include "gfx950_prims.h"
+#include "launch_once.h"
 #include "tile_schedule.h"
 
 namespace {
@@ -585,22 +586,17 @@ int launch(const AttnLaunchArgs& a)
     constexpr int BM = NW * MB * 32;
     constexpr int smem = STAGES * 2 * BN * D * 2;
     auto kern = attn_fwd_kernel<DTYPE, D, NW, MB, BN, STAGES, CAUSAL, PERSIST>;
-    static bool attr_set = false;   // idempotent; a race only repeats the call
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return -1;
-        attr_set = true;
-    }
+    static PerDeviceOnce once;                  // the attribute belongs to the (kernel, device) pair
+    const int dev = once.prepare(reinterpret_cast<const void*>(kern), smem);
+    if (dev < 0) return -1;
     const int nqt = (a.N + BM - 1) / BM;
     const long long total = (long long)nqt * a.B * a.H;
     // Persistent launch: as many workgroups as the chip holds at once (one per CU at d = 128: the LDS
     // ring takes 128 KiB), each walking its share of the tile schedule.
     long long grid = total;
     if (PERSIST) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
-            return -1;
+        const int cus = once.compute_units(dev);
+        if (cus < 8) return -1;
         const long long resident = (long long)cus * ((160 * 1024) / smem);
         if (grid > resident) grid = resident;
     }
@@ -640,6 +636,7 @@ int launch_d(const AttnLaunchArgs& a)
 
 int attn_launch(const AttnLaunchArgs& a)
 {
+    if (ATTN_CFG_PIPE && a.d == 128) return attn_pipe_launch(a);
     if (a.dtype == 0) return a.d == 128 ? launch_d<0, 128>(a) : launch_d<0, 64>(a);
     return a.d == 128 ? launch_d<1, 128>(a) : launch_d<1, 64>(a);
 }
@@ -655,6 +652,15 @@ int attn_launch_tile_param(int d, int causal, int which)
 {
     (void)causal;
     if (d != 64 && d != 128) return -1;
+    if (ATTN_CFG_PIPE && d == 128) {
+        switch (which) {
+            case 0: return 256;
+            case 1: return 64;
+            case 2: return 5;
+            case 3: return ATTNP_CFG_NW * 64;
+            default: return -1;
+        }
+    }
     switch (which) {
         case 0: return ATTN_CFG_NW * (d == 64 ? ATTN_CFG_MB_D64 : ATTN_CFG_MB) * 32;
         case 1: return ATTN_CFG_BN;

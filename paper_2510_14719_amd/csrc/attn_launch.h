@@ -18,6 +18,17 @@
 #define ATTN_CFG_STAGES 4    // LDS ring depth
 #endif
 
+// Schedule of the 16-bit kernel at d = 128: 1 = the in-wave pipeline (attn_fwd_pipe_kernel.hip: every wave
+// interleaves the softmax of one tile with the MFMAs of its neighbours), 0 = two wave groups half a
+// period apart (attn_fwd_kernel.hip), which also serves d = 64.
+#ifndef ATTN_CFG_PIPE
+#define ATTN_CFG_PIPE 0
+#endif
+// Waves per workgroup of the in-wave pipeline: 4 (one per SIMD, 64 query rows each) or 8 (32 rows each).
+#ifndef ATTNP_CFG_NW
+#define ATTNP_CFG_NW 4
+#endif
+
 // Keys per K/V tile of the 8-bit-float kernel, by head dimension.
 #ifndef ATTN8_CFG_BN_D128
 #define ATTN8_CFG_BN_D128 64
@@ -49,6 +60,9 @@ int attn_launch(const AttnLaunchArgs& a);
 
 // Query rows per workgroup (0), keys per tile (1), LDS stages (2), threads per workgroup (3).
 int attn_launch_tile_param(int d, int causal, int which);
+
+// The in-wave pipelined kernel (attn_fwd_pipe_kernel.hip), d = 128 only; same contract as attn_launch.
+int attn_pipe_launch(const AttnLaunchArgs& a);
 
 // The same for the kernel that takes Q, K, V in E4M3 (attn_fwd_fp8_kernel.hip); a.dtype is the type of O.
 int attn_fp8_launch(const AttnLaunchArgs& a);

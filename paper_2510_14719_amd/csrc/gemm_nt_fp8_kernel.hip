@@ -31,6 +31,7 @@
 
 #include "gemm_launch.h"
 #include "gfx950_prims.h"
+#include "launch_once.h"
 #include "tile_schedule.h"
 
 namespace {
@@ -356,12 +357,8 @@ int launch8(const GemmLaunchArgs& a)
 {
     constexpr int smem = stages_of(PAIRED) * H_STAGE_BYTES;
     auto kern = gemm_nt_fp8_kernel<OUT, NW, PAIRED>;
-    static bool attr_set = false;   // idempotent; a race only repeats the call
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return -1;
-        attr_set = true;
-    }
+    static PerDeviceOnce once;                  // the attribute belongs to the (kernel, device) pair
+    if (once.prepare(reinterpret_cast<const void*>(kern), smem) < 0) return -1;
     const uint8_t* A = (const uint8_t*)a.a;
     const uint8_t* B = (const uint8_t*)a.b;
     uint16_t* C = (uint16_t*)a.c;

@@ -38,6 +38,7 @@
 
 #include "gemm_launch.h"
 #include "gfx950_prims.h"
+#include "launch_once.h"
 #include "tile_schedule.h"
 
 namespace {
@@ -387,12 +388,8 @@ int launch(const GemmLaunchArgs& a)
 {
     constexpr int smem = g_stages_of(PAIRED) * G_STAGE_BYTES;
     auto kern = gemm_nt_kernel<DTYPE, NW, PAIRED>;
-    static bool attr_set = false;   // idempotent; a race only repeats the call
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return -1;
-        attr_set = true;
-    }
+    static PerDeviceOnce once;                  // the attribute belongs to the (kernel, device) pair
+    if (once.prepare(reinterpret_cast<const void*>(kern), smem) < 0) return -1;
     const uint16_t* A = (const uint16_t*)a.a;
     const uint16_t* B = (const uint16_t*)a.b;
     uint16_t* C = (uint16_t*)a.c;

@@ -64,7 +64,7 @@ __device__ __forceinline__ void dma16(const void* gbase, unsigned voff, unsigned
     // (base and LDS address are wave-uniform; the readfirstlanes are free when the compiler already
     // holds them in scalar registers and put them there when it chose vector registers)
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(uniform_ptr(gbase)) : "memory");
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(uniform_ptr(gbase)) : "memory", "m0");
 }
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() {

@@ -21,24 +21,41 @@ def bits_to_f64(t: torch.Tensor, dtype: int) -> np.ndarray:
     return tt.to(torch.float64).cpu().numpy()
 
 
+# Fill patterns of the output buffers before a launch: a NaN in fp16 and in bf16 (0x7FFF) and a float NaN with
+# a recognisable payload.  Whatever the kernel does not write stays NaN, so "every element is finite"
+# afterwards proves that every element was written; the guard margins must keep the exact patterns.
+O_FILL = 0x7FFF
+LSE_FILL_BITS = 0x7FC0BEEF
+
+
+def fresh_outputs(n_o: int, n_l: int, pad: int):
+    """(O buffer int16, LSE buffer float32, O view, LSE view): NaN-filled, with ``pad`` guard elements on each side."""
+    obuf = torch.full((n_o + 2 * pad,), O_FILL, dtype=torch.int16, device="cuda")
+    lbuf = torch.full((n_l + 2 * pad,), LSE_FILL_BITS, dtype=torch.int32, device="cuda").view(torch.float32)
+    return obuf, lbuf, obuf[pad:pad + n_o], lbuf[pad:pad + n_l]
+
+
+def check_guards(obuf, lbuf, n_o: int, n_l: int, pad: int):
+    if pad == 0:
+        return
+    li = lbuf.view(torch.int32)
+    assert bool((obuf[:pad] == O_FILL).all()) and bool((obuf[pad + n_o:] == O_FILL).all()), "O guard words overwritten"
+    assert bool((li[:pad] == LSE_FILL_BITS).all()) and bool((li[pad + n_l:] == LSE_FILL_BITS).all()), "LSE guard words overwritten"
+
+
 def run_gpu(q, k, v, dtype, scale, causal, guard=True):
     """Launch the library on [B,H,N,d] uint16 numpy inputs.  Returns (O f64, LSE f64).
 
-    With ``guard`` the outputs sit inside larger buffers whose margins are checked
-    for stray writes."""
+    The outputs start out as NaN (an unwritten element stays NaN and fails the finiteness check of
+    ``check``); with ``guard`` they sit inside larger buffers whose margins are checked for stray writes."""
     B, H, N, d = q.shape
     dq, dk, dv = to_device_bits(q), to_device_bits(k), to_device_bits(v)
     n_o, n_l = B * H * N * d, B * H * N
     pad = 256 if guard else 0
-    obuf = torch.full((n_o + 2 * pad,), 0x7B7B, dtype=torch.int16, device="cuda")
-    lbuf = torch.full((n_l + 2 * pad,), -777.0, dtype=torch.float32, device="cuda")
-    o = obuf[pad:pad + n_o]
-    lse = lbuf[pad:pad + n_l]
+    obuf, lbuf, o, lse = fresh_outputs(n_o, n_l, pad)
     binding.attn_fwd(dq, dk, dv, o, lse, B, H, N, d, scale, causal, dtype=dtype)
     torch.cuda.synchronize()
-    if guard:
-        assert bool((obuf[:pad] == 0x7B7B).all()) and bool((obuf[pad + n_o:] == 0x7B7B).all()), "O guard words overwritten"
-        assert bool((lbuf[:pad] == -777.0).all()) and bool((lbuf[pad + n_l:] == -777.0).all()), "LSE guard words overwritten"
+    check_guards(obuf, lbuf, n_o, n_l, pad)
     return bits_to_f64(o.reshape(B, H, N, d), dtype), lse.reshape(B, H, N).to(torch.float64).cpu().numpy()
 
 
@@ -62,14 +79,10 @@ def run_gpu_fp8(q, k, v, out_dtype, scale, causal):
     dq, dk, dv = (torch.from_numpy(x).cuda() for x in (q, k, v))
     n_o, n_l = B * H * N * d, B * H * N
     pad = 256
-    obuf = torch.full((n_o + 2 * pad,), 0x7B7B, dtype=torch.int16, device="cuda")
-    lbuf = torch.full((n_l + 2 * pad,), -777.0, dtype=torch.float32, device="cuda")
-    o = obuf[pad:pad + n_o]
-    lse = lbuf[pad:pad + n_l]
+    obuf, lbuf, o, lse = fresh_outputs(n_o, n_l, pad)
     binding.attn_fwd_fp8(dq, dk, dv, o, lse, B, H, N, d, scale, causal, out_dtype=out_dtype)
     torch.cuda.synchronize()
-    assert bool((obuf[:pad] == 0x7B7B).all()) and bool((obuf[pad + n_o:] == 0x7B7B).all()), "O guard words overwritten"
-    assert bool((lbuf[:pad] == -777.0).all()) and bool((lbuf[pad + n_l:] == -777.0).all()), "LSE guard words overwritten"
+    check_guards(obuf, lbuf, n_o, n_l, pad)
     return bits_to_f64(o.reshape(B, H, N, d), out_dtype), lse.reshape(B, H, N).to(torch.float64).cpu().numpy()
 
 

@@ -26,17 +26,19 @@ def env():
     return torch, binding, gemm_ref
 
 
-def run_gpu(env, a, b, dtype, pad=512, config=None):
+def run_gpu(env, a, b, dtype, pad=512, config=None, finite=True):
     torch, binding, _ = env
     M, K = a.shape
     N = b.shape[0]
     da = torch.from_numpy(a.view(np.int16)).cuda()
     db = torch.from_numpy(b.view(np.int16)).cuda()
-    buf = torch.full((M * N + 2 * pad,), 0x7B7B, dtype=torch.int16, device="cuda")
+    buf = torch.full((M * N + 2 * pad,), 0x7FFF, dtype=torch.int16, device="cuda")
     c = buf[pad:pad + M * N]
     binding.gemm_nt(da, db, c, M, N, K, dtype=dtype, config=config)
     torch.cuda.synchronize()
-    assert bool((buf[:pad] == 0x7B7B).all()) and bool((buf[pad + M * N:] == 0x7B7B).all()), "guard words overwritten"
+    assert bool((buf[:pad] == 0x7FFF).all()) and bool((buf[pad + M * N:] == 0x7FFF).all()), "guard words overwritten"
+    # (the buffer started out as NaN patterns: a finite C proves that every element was written)
+    assert bool(torch.isfinite(c.view(torch.bfloat16 if dtype == I.BF16 else torch.float16)).all()) or not finite, "an element of C was never written"
     cc = c.view(torch.bfloat16 if dtype == I.BF16 else torch.float16).reshape(M, N)
     return cc
 

@@ -33,16 +33,18 @@ def env():
     return torch, binding, gemm_ref
 
 
-def run_gpu(env, a, b, out_dtype, pad=512, config=None):
+def run_gpu(env, a, b, out_dtype, pad=512, config=None, finite=True):
     torch, binding, _ = env
     M, K = a.shape
     N = b.shape[0]
     da, db = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()
-    buf = torch.full((M * N + 2 * pad,), 0x7B7B, dtype=torch.int16, device="cuda")
+    buf = torch.full((M * N + 2 * pad,), 0x7FFF, dtype=torch.int16, device="cuda")
     c = buf[pad:pad + M * N]
     binding.gemm_nt_fp8(da, db, c, M, N, K, out_dtype=out_dtype, config=config)
     torch.cuda.synchronize()
-    assert bool((buf[:pad] == 0x7B7B).all()) and bool((buf[pad + M * N:] == 0x7B7B).all()), "guard words overwritten"
+    assert bool((buf[:pad] == 0x7FFF).all()) and bool((buf[pad + M * N:] == 0x7FFF).all()), "guard words overwritten"
+    # (the buffer started out as NaN patterns: a finite C proves that every element was written)
+    assert bool(torch.isfinite(c.view(torch.bfloat16 if out_dtype == I.BF16 else torch.float16)).all()) or not finite, "an element of C was never written"
     return c.view(torch.bfloat16 if out_dtype == I.BF16 else torch.float16).reshape(M, N)
 
 
@@ -138,7 +140,7 @@ def test_extreme_values_do_not_overflow_the_accumulator(env):
     ref = G.gemm_nt(a, b, I.E4M3)
     c = run_gpu(env, a, b, I.BF16).double().cpu().numpy()
     assert np.abs(c - ref).max() <= 2.0 ** -8 * np.abs(ref).max()
-    c16 = run_gpu(env, a, b, I.FP16).double().cpu().numpy()
+    c16 = run_gpu(env, a, b, I.FP16, finite=False).double().cpu().numpy()
     assert np.isinf(c16).all() and np.array_equal(np.sign(c16), np.sign(ref))
 
 
@@ -162,7 +164,7 @@ def test_nan_operands_poison_their_row_and_column_only(env):
     a[17, 5] = 0x7F                      # NaN in row 17 of A
     b[258, 127] = 0xFF                   # NaN in row 258 of B = column 258 of C
     ref = G.gemm_nt(a, b, I.E4M3)
-    c = run_gpu(env, a, b, I.FP16).double().cpu().numpy()
+    c = run_gpu(env, a, b, I.FP16, finite=False).double().cpu().numpy()
     want_nan = np.zeros((M, N), dtype=bool)
     want_nan[17, :] = True
     want_nan[:, 258] = True

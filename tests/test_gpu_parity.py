@@ -79,6 +79,23 @@ def test_benchmark_configs_sampled_rows(G, oracle, name):
     _sampled(G, oracle, name, 192)
 
 
+# ------------------------------------------------------------ the two largest configurations, whole heads
+@pytest.mark.parametrize("name", ["c4", "c5"])
+def test_whole_heads_of_the_large_configs(G, oracle, name):
+    """Full size, the launch configuration ``bench.py`` times: every element of O and LSE was written (the buffers
+    start out as NaN), and the first and the last (batch, head) agree with the oracle element by element."""
+    w = I.WORKLOADS[name]
+    print("config %s whole heads: B%d H%d N%d d%d dtype%d causal%d peaky%d" % (name, w.B, w.H, w.N, w.d, w.dtype, w.causal, w.peaky), flush=True)
+    q, k, v = I.make_workload(w)
+    o, l = G.run_gpu(q, k, v, w.dtype, w.scale, w.causal)
+    assert np.isfinite(o).all() and np.isfinite(l).all(), "an element of O or LSE was never written"
+    for (b, h) in [(0, 0), (w.B - 1, w.H - 1)]:
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        o_ref, l_ref = oracle.attn_ref(np.ascontiguousarray(q[sl]), np.ascontiguousarray(k[sl]), np.ascontiguousarray(v[sl]),
+                                       w.dtype, w.scale, w.causal)
+        G.check(o[sl], l[sl], o_ref, l_ref, "%s head (%d,%d)" % (name, b, h))
+
+
 # ------------------------------------------------------------ properties that hold at any size
 def test_c4_properties(G):
     """Non-causal: permuting K and V rows together leaves O and LSE unchanged (up to rounding order)."""
