@@ -12,6 +12,7 @@ from __future__ import annotations
 
 import hashlib
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -44,21 +45,38 @@ def _run(cmd, verbose):
         print(log)
 
 
+def _text_with_includes(path: str, seen=None) -> str:
+    """The text of a source and of every header of this library it includes (directly or not)."""
+    seen = set() if seen is None else seen
+    if path in seen or not os.path.exists(path):
+        return ""
+    seen.add(path)
+    text = open(path).read()
+    for name in re.findall(r'#include\s+"([^"]+)"', text):
+        for d in (CSRC, INCLUDE):
+            text += _text_with_includes(os.path.join(d, name), seen)
+    return text
+
+
 def build(extra_defines=(), out: str = LIB, verbose: bool = False, force: bool = False, jobs: int = 8) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    flags = [*HIPCC_FLAGS, "-I", INCLUDE, "-I", CSRC] + ["-D%s" % d for d in extra_defines]
-    tag = hashlib.sha1(" ".join([hipcc] + flags).encode()).hexdigest()[:12]
-    odir = os.path.join(OBJ_DIR, tag)
-    os.makedirs(odir, exist_ok=True)
+    base = [*HIPCC_FLAGS, "-I", INCLUDE, "-I", CSRC]
     headers = [os.path.join(d, f) for d in (CSRC, INCLUDE) for f in os.listdir(d) if f.endswith(".h")]
     newest_header = max(os.path.getmtime(h) for h in headers)
 
     def compile_one(src):
-        obj = os.path.join(odir, src + ".o")
         path = os.path.join(CSRC, src)
+        # a define only matters to the sources that mention its macro: the others share their objects with the
+        # default build (a sweep variant then recompiles one or two files, not the library)
+        text = _text_with_includes(path)
+        flags = base + ["-D%s" % d for d in extra_defines if re.search(r"\b%s\b" % re.escape(d.split("=")[0]), text)]
+        tag = hashlib.sha1(" ".join([hipcc] + flags).encode()).hexdigest()[:12]
+        odir = os.path.join(OBJ_DIR, tag)
+        os.makedirs(odir, exist_ok=True)
+        obj = os.path.join(odir, src + ".o")
         if not force and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(path), newest_header):
             return obj
-        tmp = obj + ".tmp.%d" % os.getpid()
+        tmp = obj + ".tmp.%d.%d" % (os.getpid(), abs(hash(out)) % 100000)
         _run([hipcc, *flags, "-x", "hip", "-c", path, "-o", tmp], verbose)
         os.replace(tmp, obj)
         return obj

@@ -26,7 +26,7 @@
 #endif
 // Waves per workgroup of the in-wave pipeline: 4 (one per SIMD, 64 query rows each) or 8 (32 rows each).
 #ifndef ATTNP_CFG_NW
-#define ATTNP_CFG_NW 4
+#define ATTNP_CFG_NW 8
 #endif
 
 // Keys per K/V tile of the 8-bit-float kernel, by head dimension.
