@@ -86,6 +86,17 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
  * probabilities, so every output row is a convex combination of V rows; LSE is the natural log of
  * that same sum (plus the reference maximum).  All other arguments, the alignment rule, ownership,
  * asynchrony and the return codes are those of attn_fwd.
+ *
+ * Numeric contract of the rounding of P (what a caller, or a test, may rely on).  The probabilities are rounded
+ * relative to a per-row reference r that the kernel keeps while it walks the keys: r is a score of the row
+ * that has really occurred, never above the running maximum and at most 8 powers of two (a factor 2^8 in the
+ * probabilities) below it; it only moves up, by taking the value of the running maximum, when that
+ * maximum has grown by more than 2^8 since r was set.  Every weight exp(s - r) <= 2^8 is rounded to E4M3 with
+ * round-to-nearest-even: relative error at most 2^-4 for values down to 2^-6 (the smallest normal number),
+ * absolute error at most 2^-10 below that (the spacing of the subnormals is 2^-9), zero below 2^-10.  In
+ * terms of the exact normalised probabilities p_j of a row the weight given to key j is therefore off by at
+ * most min(p_j, max(2^-4 p_j, 2^-10 max_j p_j)) before normalisation; the 2^-10 term is the one that
+ * depends on the 2^8 window.
  */
 int attn_fwd_fp8(const void *q, const void *k, const void *v, void *o, float *lse,
                  int B, int H, int N, int d, float scale, int causal, void *stream, int out_dtype);

@@ -61,7 +61,7 @@ def _text_with_includes(path: str, seen=None) -> str:
 def build(extra_defines=(), out: str = LIB, verbose: bool = False, force: bool = False, jobs: int = 8) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     base = [*HIPCC_FLAGS, "-I", INCLUDE, "-I", CSRC]
-    headers = [os.path.join(d, f) for d in (CSRC, INCLUDE) for f in os.listdir(d) if f.endswith(".h")]
+    headers = [os.path.join(d, f) for d in (CSRC, INCLUDE) for f in os.listdir(d) if f.endswith((".h", ".inc"))]
     newest_header = max(os.path.getmtime(h) for h in headers)
 
     def compile_one(src):
@@ -80,6 +80,11 @@ def build(extra_defines=(), out: str = LIB, verbose: bool = False, force: bool =
         _run([hipcc, *flags, "-x", "hip", "-c", path, "-o", tmp], verbose)
         os.replace(tmp, obj)
         return obj
+
+    # the assembly loop of the 64-rows-per-wave attention kernel is generated text: refresh it when its generator is newer
+    gen, inc = os.path.join(CSRC, "gen_attn_mb2_loop.py"), os.path.join(CSRC, "attn_mb2_loop.inc")
+    if not os.path.exists(inc) or os.path.getmtime(inc) < os.path.getmtime(gen):
+        _run([sys.executable, gen, inc], verbose)
 
     with ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:
         objs = list(pool.map(compile_one, SOURCES))

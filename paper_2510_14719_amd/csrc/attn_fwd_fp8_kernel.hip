@@ -213,23 +213,23 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
         }
     };
 
-    // ---- prologue: Q fragments into registers, then the whole ring in flight.  The Q loads are
-    // written as asm so that the compiler does not wait for them (its s_waitcnt vmcnt(0) would also
-    // wait for every copy issued after them); the wait below covers them, they were issued first.
+    // ---- prologue: the whole ring in flight, then the Q fragments into registers.  The Q loads are ordinary
+    // loads issued after the copies and waited for together with them: the compiler must know that their
+    // destination registers are busy until the data is there (a load hidden in an asm statement lets it move or
+    // reuse those registers while the load is still in flight).
+#pragma unroll
+    for (int s0 = -2; s0 < AHEAD; ++s0) issue_stage(s0);
     i32x8 Qf[FK];                               // B operand of T: query lane%32, features fk*64 + (lane/32)*32 .. +31
     {
         const int row = min(wq0 + lr, N - 1);
         const uint8_t* qr = qh + (size_t)row * D + g * 32;
 #pragma unroll
         for (int fk = 0; fk < FK; ++fk) {
-            i32x4 lo, hi;
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(lo) : "v"(qr + fk * 64) : "memory");
-            asm volatile("global_load_dwordx4 %0, %1, off offset:16" : "=&v"(hi) : "v"(qr + fk * 64) : "memory");
+            const i32x4 lo = *reinterpret_cast<const i32x4*>(qr + fk * 64);
+            const i32x4 hi = *reinterpret_cast<const i32x4*>(qr + fk * 64 + 16);
             Qf[fk] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         }
     }
-#pragma unroll
-    for (int s0 = -2; s0 < AHEAD; ++s0) issue_stage(s0);
 
     // A operand of the ones block: 1.0 in every byte, kept in registers for the whole kernel
     i32x8 ones;
@@ -247,34 +247,33 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     // ---- per-lane LDS read offsets (the rest of every address is an immediate)
     // K fragment (A operand of T): key kb*32 + lane%32, features fk*64 + (lane/32)*32 .. +31 = columns
     // fk*4 + g*2 and the next one, each at its permuted slot.
-    int k_lane[FK][2];
-#pragma unroll
-    for (int fk = 0; fk < FK; ++fk)
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-            k_lane[fk][h] = lr * D + (((fk * 4 + g * 2 + h) ^ ((lr / RPB) % CPR)) * 16);
-    // V^T fragment (A operand of U): feature db*32 + lane%32; a transposing read hands lane i of a
-    // 16-lane group byte i of the 8 rows that the group's lane pairs (2e, 2e+1) address.  The rows
-    // are positions 16 r + 8 g + e, which hold the keys of P words 2r and 2r+1 of this lane group.
-    int v_lane[DB];
+    // All of a lane's fragment addresses inside a stage differ from ONE per-lane offset by an XOR with a
+    // compile-time constant (the permuted 16-byte slot is column ^ f(row), and the column bits that vary
+    // with the fragment are disjoint from those that vary with the lane), and a stage starts on a 1 KiB
+    // boundary: (stage + offset) ^ constant is the address, one register per tile kind instead of one per
+    // fragment column.
+    const int k_lane0 = lr * D + (((g * 2) ^ ((lr / RPB) % CPR)) * 16);
+    int v_lane0;
     {
         const int e = (lane & 15) >> 1, fh = (lane >> 4) & 1;
         const int p = g * 8 + e;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-            v_lane[db] = TILE_BYTES + p * D + (((db * 2 + fh) ^ (2 * ((p / RPB) % (CPR / 2)))) * 16) + (lane & 1) * 8;
+        v_lane0 = TILE_BYTES + p * D + ((fh ^ (2 * ((p / RPB) % (CPR / 2)))) * 16) + (lane & 1) * 8;
     }
+    // (32-bit LDS addresses throughout: an XOR on a generic pointer would hide the address space from the compiler)
+    auto lds_addr = [](const char* st, int off0, unsigned c) __attribute__((always_inline)) -> unsigned {
+        return ((unsigned)(size_t)(LDS_AS const char*)st + (unsigned)off0) ^ c;
+    };
     auto read_kf = [&](const char* st, int kb, int fk) __attribute__((always_inline)) -> i32x8 {
-        const i32x4 lo = *reinterpret_cast<const i32x4*>(st + k_lane[fk][0] + kb * 32 * D);
-        const i32x4 hi = *reinterpret_cast<const i32x4*>(st + k_lane[fk][1] + kb * 32 * D);
+        const i32x4 lo = *(LDS_AS const i32x4*)(size_t)(lds_addr(st, k_lane0, (fk * 4) * 16) + kb * 32 * D);
+        const i32x4 hi = *(LDS_AS const i32x4*)(size_t)(lds_addr(st, k_lane0, (fk * 4 + 1) * 16) + kb * 32 * D);
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
     auto read_vf = [&](const char* st, int kc, int db) __attribute__((always_inline)) -> i32x8 {
-        const char* a = st + v_lane[db] + kc * 64 * D;
-        const i32x2 r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a));
-        const i32x2 r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a + 16 * D));
-        const i32x2 r2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a + 32 * D));
-        const i32x2 r3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(a + 48 * D));
+        const unsigned a = lds_addr(st, v_lane0, (db * 2) * 16) + kc * 64 * D;
+        const i32x2 r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(size_t)(a));
+        const i32x2 r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(size_t)(a + 16 * D));
+        const i32x2 r2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(size_t)(a + 32 * D));
+        const i32x2 r3 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(size_t)(a + 48 * D));
         const i32x4 lo = __builtin_shufflevector(r0, r1, 0, 1, 2, 3);
         const i32x4 hi = __builtin_shufflevector(r2, r3, 0, 1, 2, 3);
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -437,14 +436,14 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     };
     auto stage_ptr = [&](int s) __attribute__((always_inline)) -> const char* { return smem + ((s + 2 * STAGES) % STAGES) * STAGE_BYTES; };
 
-    // The Q fragments and the stages up to 0 (everything issued before the last AHEAD - 1 stages).
-    wait_vmcnt<(AHEAD - 1) * PPW>();
-    // (tell the compiler that the Q registers are written by now; word by word: the host pass of the
-    // compiler silently drops a kernel whose inline asm takes a 256-bit operand)
+    // Use the Q fragments once here: the compiler then waits for their loads now (its vmcnt(0) also covers the
+    // copies issued before them) instead of inside the first pass.  (Word by word: the host pass of the compiler
+    // silently drops a kernel whose inline asm takes a 256-bit operand.)
 #pragma unroll
     for (int fk = 0; fk < FK; ++fk)
 #pragma unroll
-        for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(Qf[fk][t]));
+        for (int t = 0; t < 8; ++t) asm volatile("" :: "v"(Qf[fk][t]));
+    wait_vmcnt<0>();
     m_run = -__builtin_inff();
     L = f32x16(0.f);
 #pragma unroll

@@ -62,6 +62,11 @@ constexpr float RESCALE_LOG2 = 8.0f;
 #define ATTN_PERSIST_NC_MAX_N 1024
 #endif
 
+// 1: the causal d = 64 launch is persistent as well (measured on MI355X: see launch_d).
+#ifndef ATTN_PERSISTENT_D64
+#define ATTN_PERSISTENT_D64 1
+#endif
+
 // Which wave group issues the global -> LDS copies (see COPY_WAVES in the kernel).
 #ifndef ATTN_COPY_GROUP
 #define ATTN_COPY_GROUP 0
@@ -629,6 +634,7 @@ int launch_d(const AttnLaunchArgs& a)
         if (a.causal) return launch<DTYPE, D, NW, MB, BN, STAGES, true, true>(a);
         if (a.N <= ATTN_PERSIST_NC_MAX_N) return launch<DTYPE, D, NW, MB, BN, STAGES, false, true>(a);
     }
+    if (D == 64 && ATTN_PERSISTENT_D64 && a.causal) return launch<DTYPE, D, NW, MB, BN, STAGES, true, true>(a);
     return a.causal ? launch<DTYPE, D, NW, MB, BN, STAGES, true, false>(a) : launch<DTYPE, D, NW, MB, BN, STAGES, false, false>(a);
 }
 

@@ -52,11 +52,10 @@ namespace {
 #ifndef ATTNP_COPIES_IN_PASS
 #define ATTNP_COPIES_IN_PASS 1
 #endif
-// Independent accumulation chains of a row sum.
-#ifndef ATTNP_SUMCHAINS
-#define ATTNP_SUMCHAINS 1
+// 1: with four waves of 64 rows the steady state runs in the generated assembly loop (attn_mb2_loop.inc); 0: in C++.
+#ifndef ATTNP_ASM_LOOP
+#define ATTNP_ASM_LOOP 1
 #endif
-
 #ifdef ATTNP_TIMING
 // Profiling builds only: cycle and wall-clock totals of the main loop of the first workgroups.
 constexpr int DBGP_WGS = 1024, DBGP_SLOTS = 8;
@@ -97,26 +96,31 @@ __device__ __forceinline__ float pipe_xor32_sum(float x) {
     return a + b;
 }
 
-// The first contraction's MFMA with explicit register classes, for the 64-rows-per-wave form: result in
-// vector registers (the vector ALU reads it), Q operand in accumulation registers.  The compiler picks one
-// register class for the results of all MFMA builtins of a function (accumulation registers as soon as a wave
-// may use more than 256 registers) and would then copy every score to a vector register, one instruction
-// each.  It does not see what these statements are: it inserts the waits for their LDS operands, but not the
-// wait states an MFMA result needs before a vector instruction reads it; the callers keep a whole pass
-// (or explicit s_nops) between the two.
-template <int DTYPE>
-__device__ __forceinline__ void mfma_t_asm(f32x16& acc, s16x8 kf, s16x8 qf, bool first) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    if (first) {
-        if (DTYPE == 0) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(acc) : "v"(kf), "a"(qf));
-        else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(kf), "a"(qf));
-    } else {
-        if (DTYPE == 0) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(kf), "a"(qf));
-        else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(kf), "a"(qf));
-    }
-#else
-    (void)acc; (void)kf; (void)qf; (void)first;
-#endif
+// The steady-state loop of the 64-rows-per-wave form as hand-scheduled assembly (gen_attn_mb2_loop.py writes it and
+// documents its register contract).
+#include "attn_mb2_loop.inc"
+
+typedef float f32x32 __attribute__((ext_vector_type(32)));
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x32 __attribute__((ext_vector_type(32)));
+
+__device__ __forceinline__ f32x32 cat32(f32x16 a, f32x16 b) {
+    return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31);
+}
+__device__ __forceinline__ f32x16 lo16(f32x32 x) { return __builtin_shufflevector(x, x, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15); }
+__device__ __forceinline__ f32x16 hi16(f32x32 x) { return __builtin_shufflevector(x, x, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31); }
+__device__ __forceinline__ i32x32 cat8x4(const s16x8* f) {       // eight 4-register fragments -> one 32-register tuple
+    i32x4 w[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[i] = __builtin_bit_cast(i32x4, f[i]);
+    const i32x8 a = __builtin_shufflevector(w[0], w[1], 0, 1, 2, 3, 4, 5, 6, 7), b = __builtin_shufflevector(w[2], w[3], 0, 1, 2, 3, 4, 5, 6, 7);
+    const i32x8 c = __builtin_shufflevector(w[4], w[5], 0, 1, 2, 3, 4, 5, 6, 7), d = __builtin_shufflevector(w[6], w[7], 0, 1, 2, 3, 4, 5, 6, 7);
+    const i32x16 ab = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+    const i32x16 cd = __builtin_shufflevector(c, d, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+    return __builtin_shufflevector(ab, cd, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31);
 }
 
 template <int DTYPE, int D, int NW, int MB, bool CAUSAL>
@@ -126,7 +130,7 @@ void attn_fwd_pipe_kernel(const uint16_t* __restrict__ q, const uint16_t* __rest
                           float scale, float scale_log2e)
 {
     typedef Elem<DTYPE> E;
-    constexpr int BN = 64, STAGES = 5, AHEAD = 2;
+    constexpr int BN = 64, STAGES = 4, AHEAD = 2;
     constexpr int BM = NW * MB * 32;            // query rows per workgroup
     constexpr int KB = BN / 32;                 // 32-key blocks per K/V tile
     constexpr int KK = D / 16;                  // contraction steps of Q K^T
@@ -140,7 +144,7 @@ void attn_fwd_pipe_kernel(const uint16_t* __restrict__ q, const uint16_t* __rest
     constexpr int LPG = 2 * CPW;                // copies a wave issues per stage (K pieces, then V pieces)
     static_assert(CHUNKS % NW == 0 && CPW >= 1, "a tile must split evenly over the waves");
     static_assert(BN % (MB * 32) == 0, "only a wave's last tile may need a mask");
-    constexpr bool ASM_T = MB > 1;              // see mfma_t_asm
+    constexpr bool ASM_LOOP = MB == 2 && NW == 4 && D == 128 && ATTNP_ASM_LOOP;   // the steady state as the generated assembly loop
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const unsigned lds_base = (unsigned)(size_t)(LDS_AS void*)smem;
@@ -219,20 +223,21 @@ void attn_fwd_pipe_kernel(const uint16_t* __restrict__ q, const uint16_t* __rest
         }
     };
 
-    // ---- prologue: Q fragments into registers, then the whole ring in flight.  The Q loads are asm
-    // so that the compiler does not wait for them with a vmcnt(0) of its own (which would also wait
-    // for every copy issued after them); the counted wait below covers them, they were issued first.
+    // ---- prologue: the whole ring in flight, then the Q fragments into registers.  The Q loads are ordinary
+    // loads issued AFTER the copies, followed by a wait for everything: the compiler must know that their
+    // destination registers are busy until the data is there.  (Loads hidden in asm statements would let it
+    // move or reuse those registers while the loads are still in flight: with 64 rows per wave it did, and a
+    // late Q fragment landed in the register that held a copy's address offset.)
+#pragma unroll
+    for (int s0 = -2; s0 < AHEAD; ++s0) issue_stage(s0);
     s16x8 Qf[MB][KK];                           // B operand of T: query lane%32, features (kk*2 + lane/32)*8 .. +7
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int row = min(wq0 + mb * 32 + lr, N - 1);
         const uint16_t* qr = qh + (size_t)row * D + g * 8;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
-            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=&v"(Qf[mb][kk]) : "v"(qr), "n"(kk * 32) : "memory");
+        for (int kk = 0; kk < KK; ++kk) Qf[mb][kk] = *reinterpret_cast<const s16x8*>(qr + kk * 16);
     }
-#pragma unroll
-    for (int s0 = -2; s0 < AHEAD; ++s0) issue_stage(s0);
 
     f32x16 O[MB][DB], S[2][MB][KB];
     unsigned pw[MB][KB * 8];                    // P as packed 16-bit pairs: one buffer, rewritten word by word behind the U that reads it
@@ -269,11 +274,10 @@ void attn_fwd_pipe_kernel(const uint16_t* __restrict__ q, const uint16_t* __rest
     // (scale-and-subtract FMA, then exp2; two independent chains), the rounding and packing of pair k-1 and the
     // row-sum update of pair k-2 (a dependent vector instruction issues a cycle or two late; a unit apart, none waits).
     constexpr int PAIRS = KB * 8;               // score pairs per lane and 32-query block
-    constexpr int FUNITS = PAIRS + 2, NUNITS = MB * FUNITS;
-    constexpr int NCH = ATTNP_SUMCHAINS;
+    constexpr int FUNITS = PAIRS + 1, NUNITS = MB * FUNITS;
+    constexpr int NCH = 2;                      // accumulation chains of a row sum
     constexpr float FAST_SUM_MAX = 16384.0f;
     float fb[MB][2], sm_sum[MB][NCH];
-    unsigned fw[MB];
     auto softmax_mask = [&](auto par, int j) __attribute__((always_inline)) {
         constexpr int P = decltype(par)::value;
         const int kv0 = tile_row(j), first = j * BN;   // the tile's first row and the first key not yet seen
@@ -293,19 +297,16 @@ void attn_fwd_pipe_kernel(const uint16_t* __restrict__ q, const uint16_t* __rest
     auto fast_unit = [&](auto par, auto uc) __attribute__((always_inline)) {
         constexpr int P = decltype(par)::value;
         constexpr int u = decltype(uc)::value, k = u / MB, mb = u % MB;   // the blocks take turns
-        if constexpr (k >= 2) {                 // row-sum update of pair k-2
-            constexpr int q = k - 2;
-            float sacc = E::add_pair(fw[mb], q < NCH ? 0.f : sm_sum[mb][q % NCH]);
-            asm volatile("" : "+v"(sacc));      // (left alone the compiler collects all row-sum updates at the end of the loop body)
-            sm_sum[mb][q % NCH] = sacc;
-        }
-        if constexpr (k >= 1 && k - 1 < PAIRS) {    // word k-1 of the block's P
+        if constexpr (k >= 1 && k - 1 < PAIRS) {    // word k-1 of the block's P, and its two probabilities into the row sum
             unsigned wd = E::pack2(fb[mb][0], fb[mb][1]);
             // (pins the word where it is written: it is only used by the next pass, and the compiler would
             // otherwise sink the conversion down to that use)
             asm volatile("" : "+v"(wd));
             pw[mb][k - 1] = wd;
-            fw[mb] = wd;
+            // (vector additions, not a v_dot2c on the packed pair: see Elem::add_pair_valu; two chains)
+            float s0 = E::add_pair_valu(wd, fb[mb][0], fb[mb][1], k - 1 < NCH ? 0.f : sm_sum[mb][(k - 1) % NCH]);
+            asm volatile("" : "+v"(s0));        // (left alone the compiler collects all row-sum updates at the end of the loop body)
+            sm_sum[mb][(k - 1) % NCH] = s0;
         }
         if constexpr (k < PAIRS) {              // the exponentials of pair k
             constexpr int kb = k / 8, t = k % 8;
@@ -347,7 +348,7 @@ void attn_fwd_pipe_kernel(const uint16_t* __restrict__ q, const uint16_t* __rest
                     const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[P][mb][kb][2 * t + 1], scale_log2e, nm));
                     const unsigned wd = E::pack2(p0, p1);
                     pw[mb][kb * 8 + t] = wd;
-                    ts[t % 2] = E::add_pair(wd, ts[t % 2]);
+                    ts[t % 2] = E::add_pair_valu(wd, p0, p1, ts[t % 2]);
                     __builtin_amdgcn_sched_barrier(0);   // (a rare path: kept narrow, so that it claims no registers of its own)
                 }
             l_run[mb] = __builtin_fmaf(l_run[mb], alpha, ts[0] + ts[1]);
@@ -409,8 +410,7 @@ void attn_fwd_pipe_kernel(const uint16_t* __restrict__ q, const uint16_t* __rest
             constexpr int f = decltype(fc)::value, mb = decltype(mbc)::value;
             if constexpr (f >= NU) {
                 constexpr int kb = (f - NU) % KB, kk = (f - NU) / KB;
-                if constexpr (ASM_T) mfma_t_asm<DTYPE>(S[P ^ 1][mb][kb], fr[f], Qf[mb][kk], kk == 0);
-                else if constexpr (kk == 0) S[P ^ 1][mb][kb] = E::mfma(fr[f], Qf[mb][kk], f32x16(0.f));
+                if constexpr (kk == 0) S[P ^ 1][mb][kb] = E::mfma(fr[f], Qf[mb][kk], f32x16(0.f));
                 else S[P ^ 1][mb][kb] = E::mfma(fr[f], Qf[mb][kk], S[P ^ 1][mb][kb]);
             } else {
                 constexpr int kb = f / (2 * DB), ks = (f / DB) % 2, db = f % DB;
@@ -473,17 +473,13 @@ void attn_fwd_pipe_kernel(const uint16_t* __restrict__ q, const uint16_t* __rest
     };
     auto stage_ptr = [&](int s) __attribute__((always_inline)) -> const char* { return smem + ((s + 2 * STAGES) % STAGES) * STAGE_BYTES; };
 
-    // The Q fragments and the stages up to 0 (everything issued before stage 1).
-    wait_vmcnt<LPG>();
+    // Use the Q fragments once here: the compiler then waits for their loads now (its vmcnt(0) also covers the
+    // copies of all four stages issued before them) instead of inside the first pass.
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            asm volatile("" : "+v"(Qf[mb][kk]));
-            // (with 64 query rows per wave the Q fragments live in the accumulation registers: the vector
-            // registers are needed for the scores and probabilities the vector ALU works on)
-            if (ASM_T) asm volatile("" : "+a"(Qf[mb][kk]));
-        }
+        for (int kk = 0; kk < KK; ++kk) asm volatile("" :: "v"(Qf[mb][kk]));
+    wait_vmcnt<0>();
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         m_run[mb] = -__builtin_inff();
@@ -510,8 +506,6 @@ void attn_fwd_pipe_kernel(const uint16_t* __restrict__ q, const uint16_t* __rest
     //   j == nt_w - 1   U_{j-1}, then C_j with the mask (diagonal or ragged end), then U_j (stage j is visible)
     //   j >= nt_w       nothing: the wave only keeps copying its share for the others
     pass(NO, Y, NO, NO, P1, stage_ptr(-2), 0);                          // T_0 into the scores of parity 0
-    // (the softmax that reads these scores may follow at once; everywhere else a whole pass lies in between)
-    if (ASM_T) asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
     int j = 0;
     if (nt_w >= 2) {
         step(0);
@@ -522,25 +516,60 @@ void attn_fwd_pipe_kernel(const uint16_t* __restrict__ q, const uint16_t* __rest
         // issued inside the passes, the fast softmax only.  A tile whose probabilities overflowed leaves the
         // loop, is redone on the slow path out here, and the loop of the matching phase is entered again.
         // (The mask never applies here: N >= BN because nt_w >= 2, and only a wave's last tile is ragged or diagonal.)
-        // One loop serves both phases: it is entered at its first half for an odd j, at its second for an even one.
         while (j <= nt_w - 2) {
             int redo = -1;                      // parity of a tile to redo
-            bool second_half = !(j & 1);
-            do {                                // bottom-tested: the accumulators are updated in place
-                if (!second_half) {
+            if (ASM_LOOP && (j & 1)) {
+#if defined(__HIP_DEVICE_COMPILE__)
+                f32x32 o0 = cat32(O[0][0], O[0][1]), o1 = cat32(O[0][2], O[0][3]), o2 = cat32(O[MB - 1][0], O[MB - 1][1]), o3 = cat32(O[MB - 1][2], O[MB - 1][3]);
+                f32x32 s0 = cat32(S[0][0][0], S[0][0][1]), s1 = cat32(S[0][MB - 1][0], S[0][MB - 1][1]);
+                f32x32 s2 = cat32(S[1][0][0], S[1][0][1]), s3 = cat32(S[1][MB - 1][0], S[1][MB - 1][1]);
+                const i32x32 q0 = cat8x4(Qf[0]), q1 = cat8x4(Qf[MB - 1]);
+                i32x32 pv;
+#pragma unroll
+                for (int i = 0; i < 32; ++i) pv[i] = (int)pw[(i / 16) % MB][i % 16];
+                f32x4v st = {negmc[0], negmc[MB - 1], l_run[0], l_run[MB - 1]};
+                const int ln = fresh_lane();
+                const int krd = k_read_off(ln), vrd = v_read_off(ln);
+                const unsigned kcp = k_copy_off(ln), vcp = v_copy_off(ln);
+                int jj = j, flag;
+                const int j_end = nt_w - 2;
+#define ATTN_MB2_OPERANDS \
+                    : "+{a[0:31]}"(o0), "+{a[32:63]}"(o1), "+{a[64:95]}"(o2), "+{a[96:127]}"(o3), \
+                      "+{v[0:31]}"(s0), "+{v[32:63]}"(s1), "+{v[64:95]}"(s2), "+{v[96:127]}"(s3), \
+                      "+{v[128:159]}"(pv), "+{v[160:163]}"(st), "+{s40}"(jj), "={s46}"(flag) \
+                    : "{a[128:159]}"(q0), "{a[160:191]}"(q1), "{s[36:37]}"(kh), "{s[38:39]}"(vh), "{s41}"(j_end), "{s42}"(scale_log2e), \
+                      "{s43}"(lds_base), "{s44}"(wave), "{s45}"(N), "{v200}"(krd), "{v201}"(vrd), "{v202}"(kcp), "{v203}"(vcp) \
+                    : ATTN_MB2_LOOP_CLOBBERS
+                if constexpr (DTYPE == 0) asm volatile(ATTN_MB2_LOOP_F16 ATTN_MB2_OPERANDS);
+                else asm volatile(ATTN_MB2_LOOP_BF16 ATTN_MB2_OPERANDS);
+#undef ATTN_MB2_OPERANDS
+                O[0][0] = lo16(o0); O[0][1] = hi16(o0); O[0][2] = lo16(o1); O[0][3] = hi16(o1);
+                O[MB - 1][0] = lo16(o2); O[MB - 1][1] = hi16(o2); O[MB - 1][2] = lo16(o3); O[MB - 1][3] = hi16(o3);
+                S[0][0][0] = lo16(s0); S[0][0][1] = hi16(s0); S[0][MB - 1][0] = lo16(s1); S[0][MB - 1][1] = hi16(s1);
+                S[1][0][0] = lo16(s2); S[1][0][1] = hi16(s2); S[1][MB - 1][0] = lo16(s3); S[1][MB - 1][1] = hi16(s3);
+#pragma unroll
+                for (int i = 0; i < 32; ++i) pw[(i / 16) % MB][i % 16] = (unsigned)pv[i];
+                negmc[0] = st[0]; negmc[MB - 1] = st[1]; l_run[0] = st[2]; l_run[MB - 1] = st[3];
+                j = jj;
+                if (flag) redo = j & 1;
+#endif
+            } else if ((j & 1) && j + 1 <= nt_w - 2) {
+                do {                            // bottom-tested: the accumulators are updated in place
                     step(j, !ATTNP_COPIES_IN_PASS);
                     if (__builtin_expect(pass(Y, Y, Y, CIP, P1, stage_ptr(j - 1), j), 0)) { redo = 1; break; }
-                    if (++j > nt_w - 2) break;
-                }
-                second_half = false;
+                    step(j + 1, !ATTNP_COPIES_IN_PASS);
+                    if (__builtin_expect(pass(Y, Y, Y, CIP, P0, stage_ptr(j), j + 1), 0)) { redo = 0; ++j; break; }
+                    j += 2;
+                } while (j + 1 <= nt_w - 2);
+            } else {
                 step(j, !ATTNP_COPIES_IN_PASS);
-                if (__builtin_expect(pass(Y, Y, Y, CIP, P0, stage_ptr(j - 1), j), 0)) { redo = 0; break; }
-                ++j;
-            } while (j <= nt_w - 2);
-            // The scores of the tile are gone by now (their registers were reused as they were consumed), but its K
-            // tile is not: stage j-2 keeps it until the copies of stage j+3 go out, after the next barrier.
-            if (redo == 1) { pass(NO, Y, NO, NO, P0, stage_ptr(j - 2), j); slow_softmax(P1); ++j; }
-            else if (redo == 0) { pass(NO, Y, NO, NO, P1, stage_ptr(j - 2), j); slow_softmax(P0); ++j; }
+                if (j & 1) { if (pass(Y, Y, Y, CIP, P1, stage_ptr(j - 1), j)) redo = 1; }
+                else { if (pass(Y, Y, Y, CIP, P0, stage_ptr(j - 1), j)) redo = 0; }
+                if (redo < 0) ++j;
+            }
+            // (the scores of the tile are still in their registers: the other parity's were written meanwhile)
+            if (redo == 1) { slow_softmax(P1); ++j; }
+            else if (redo == 0) { slow_softmax(P0); ++j; }
         }
     }
     // j == nt_w - 1: the last tile this wave computes on
@@ -597,7 +626,7 @@ template <int DTYPE, int D, int NW, int MB, bool CAUSAL>
 int launch_pipe(const AttnLaunchArgs& a)
 {
     constexpr int BM = NW * MB * 32;
-    constexpr int smem = 5 * 2 * 64 * D * 2;
+    constexpr int smem = 4 * 2 * 64 * D * 2;
     auto kern = attn_fwd_pipe_kernel<DTYPE, D, NW, MB, CAUSAL>;
     static PerDeviceOnce once;                  // the attribute belongs to the (kernel, device) pair
     if (once.prepare(reinterpret_cast<const void*>(kern), smem) < 0) return -1;

@@ -33,6 +33,14 @@ template <> struct Elem<0> {  // IEEE binary16
         const v2 one = {(_Float16)1.0f, (_Float16)1.0f};
         return __builtin_amdgcn_fdot2(__builtin_bit_cast(v2, w), one, acc, false);
     }
+    // The same update for code that sits between MFMAs of its own wave (the dot instructions go through the matrix
+    // pipe: measured on MI355X, every v_dot2c there stalls the wave's MFMA stream by a dozen cycles).  fp16: the two
+    // unrounded values are added instead; their rounding to fp16 (2^-12 relative, zero mean) is far below what
+    // the sum is used for.
+    static __device__ __forceinline__ float add_pair_valu(unsigned w, float p0, float p1, float acc) {
+        (void)w;
+        return acc + p0 + p1;
+    }
 };
 template <> struct Elem<1> {  // bfloat16
     typedef __bf16 v8 __attribute__((ext_vector_type(8)));
@@ -47,6 +55,13 @@ template <> struct Elem<1> {  // bfloat16
     static __device__ __forceinline__ float add_pair(unsigned w, float acc) {
         const v2 one = {(__bf16)1.0f, (__bf16)1.0f};
         return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2, w), one, acc, false);
+    }
+    // bf16: the ROUNDED values are added (a bf16 is the upper half of its fp32: one shift, one mask).  With 8
+    // significant bits the rounding matters: normalising by the sum of the rounded probabilities lets the
+    // rounding errors of numerator and denominator cancel on rows that a few keys dominate.
+    static __device__ __forceinline__ float add_pair_valu(unsigned w, float p0, float p1, float acc) {
+        (void)p0; (void)p1;
+        return acc + __builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u);
     }
 };
 

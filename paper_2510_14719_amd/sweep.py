@@ -19,6 +19,8 @@ What the axes stand for on gfx950:
              ATTN_CFG_PIPE      0: two wave groups half a period apart (attn_fwd_kernel.hip, the default);
                                 1: the coarse-grained pipeline of the paper's Algorithm 1 inside every wave
                                    (attn_fwd_pipe_kernel.hip): the softmax of tile j between the MFMAs of U_{j-1} and T_{j+1}
+             ATTNP_CFG_NW       (pipe only) 8 waves of 32 query rows (two per SIMD), or 4 waves of 64 rows (one per SIMD,
+                                O and Q in the accumulation registers, the steady state a generated assembly loop)
              ATTNP_INTERLEAVE   (pipe only) 1: softmax in slices between the MFMAs; 0: after them as one block
              ATTNP_FWIN         (pipe only) LDS fragments requested ahead of their MFMAs
              The 16-bit two-group kernel fixes its ring depth (4 stages: the protocol and the 160 KiB LDS), its tile
@@ -57,21 +59,23 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 VARIANT_DIR = os.path.join(HERE, "sweep_variants")
 
 GRIDS = {
-    "attn_schedule": {"ATTN_CFG_PIPE": [0, 1], "ATTNP_INTERLEAVE": [1, 0], "ATTNP_FWIN": [3, 2]},
+    "attn_schedule": {"ATTN_CFG_PIPE": [0, 1], "ATTNP_CFG_NW": [8, 4], "ATTNP_INTERLEAVE": [1, 0], "ATTNP_FWIN": [3, 2]},
     "attn": {"ATTN_FWIN": [1, 2, 4, 8], "ATTN_COPY_GROUP": [0, 2, 1], "ATTN_SUMCHAINS": [2, 4]},
     "attn_causal": {"ATTN_PERSISTENT": [0, 1], "ATTN_FWIN": [2, 4]},
     "attn_fp8": {"ATTN8_FWIN": [1, 2, 3], "ATTN8_INTERLEAVE": [1, 0], "ATTN8_STAGES": [4, 8], "ATTN8_COPIES_IN_PASS": [1, 0]},
     "gemm": {"GEMM_CONFIG": [0, 1, 2, 3, 4], "GEMM_STAGES": [4, 5], "GEMM_TAIL_READS": [3, 0]},
     "gemm_fp8": {"GEMM8_CONFIG": [0, 1, 2, 3, 4], "GEMM8_STAGES": [4, 5], "GEMM8_TAIL_READS": [3, 0]},
 }
-DEFAULTS = {"ATTN_CFG_PIPE": 0, "ATTNP_INTERLEAVE": 1, "ATTNP_FWIN": 3, "ATTN8_FWIN": 2, "ATTN8_INTERLEAVE": 1, "ATTN8_STAGES": 4, "ATTN8_COPIES_IN_PASS": 1, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
+DEFAULTS = {"ATTN_CFG_PIPE": 0, "ATTNP_CFG_NW": 8, "ATTNP_INTERLEAVE": 1, "ATTNP_FWIN": 3, "ATTN8_FWIN": 2, "ATTN8_INTERLEAVE": 1, "ATTN8_STAGES": 4, "ATTN8_COPIES_IN_PASS": 1, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
             "GEMM_STAGES": 4, "GEMM_CONFIG": 0, "GEMM_TAIL_READS": 3,
             "GEMM8_STAGES": 4, "GEMM8_TAIL_READS": 3, "GEMM8_COPY_PHASE": 1, "GEMM8_CONFIG": 0}
 
 
 # The non-default points that tests/test_gpu_sweep_variants.py checks against the oracle (two per operation).
 TEST_VARIANTS = {
-    "attn_schedule": [{"ATTN_CFG_PIPE": 1, "ATTNP_INTERLEAVE": 1, "ATTNP_FWIN": 3}, {"ATTN_CFG_PIPE": 1, "ATTNP_INTERLEAVE": 0, "ATTNP_FWIN": 2}],
+    "attn_schedule": [{"ATTN_CFG_PIPE": 1, "ATTNP_CFG_NW": 8, "ATTNP_INTERLEAVE": 1, "ATTNP_FWIN": 3},
+                      {"ATTN_CFG_PIPE": 1, "ATTNP_CFG_NW": 8, "ATTNP_INTERLEAVE": 0, "ATTNP_FWIN": 2},
+                      {"ATTN_CFG_PIPE": 1, "ATTNP_CFG_NW": 4, "ATTNP_INTERLEAVE": 1, "ATTNP_FWIN": 3}],
     "attn": [{"ATTN_FWIN": 4, "ATTN_COPY_GROUP": 2, "ATTN_SUMCHAINS": 2}, {"ATTN_FWIN": 1, "ATTN_COPY_GROUP": 1, "ATTN_SUMCHAINS": 4}],
     "attn_causal": [{"ATTN_PERSISTENT": 0, "ATTN_FWIN": 2}, {"ATTN_PERSISTENT": 1, "ATTN_FWIN": 4}],
     "attn_fp8": [{"ATTN8_FWIN": 3, "ATTN8_INTERLEAVE": 0, "ATTN8_STAGES": 4, "ATTN8_COPIES_IN_PASS": 1},
@@ -88,7 +92,10 @@ def grid_points(op: str):
     keys = list(g)
     pts = [dict(zip(keys, vals)) for vals in itertools.product(*(g[k] for k in keys))]
     if op == "attn_schedule":
-        pts = [p for p in pts if p["ATTN_CFG_PIPE"] == 1 or all(p[k] == DEFAULTS[k] for k in keys if k != "ATTN_CFG_PIPE")]
+        # the knobs of the in-wave kernel only vary where it is selected; with four waves its steady state is the
+        # generated assembly loop, which has its own fragment window and is interleaved by construction
+        pts = [p for p in pts if (p["ATTN_CFG_PIPE"] == 1 or all(p[k] == DEFAULTS[k] for k in keys if k != "ATTN_CFG_PIPE"))
+               and (p["ATTNP_CFG_NW"] == 8 or (p["ATTNP_INTERLEAVE"] == 1 and p["ATTNP_FWIN"] == 3))]
     pts.sort(key=lambda p: (not all(p[k] == DEFAULTS[k] for k in keys), [p[k] for k in keys]))
     return pts
 
