@@ -60,7 +60,7 @@ STAGE_BYTES = 2 * TILE_BYTES
 LPG = 8                     # copies per wave and stage (4 K pieces, 4 V pieces)
 RING = 8                    # fragment registers: RING fragments of 4 registers
 FWIN = 6                    # fragments requested ahead (LDS reads in flight: at most 2 * FWIN <= 15, the counter's range)
-VALU_BUDGET = 24            # vector-ALU cycles placed behind one MFMA (an MFMA occupies the pipe for 32)
+VALU_BUDGET = 28            # vector-ALU cycles placed behind one MFMA (an MFMA occupies the pipe for 32)
 VALU_BUDGET_BF16 = 34       # bf16 carries two more instructions per score pair (the rounded row sums): the vector ALU is its bound
 COST = {"fma": 5, "exp": 9, "cvt": 5, "dot": 5, "add": 5}
 
