@@ -67,6 +67,14 @@ constexpr float RESCALE_LOG2 = 8.0f;
 #define ATTN_PERSISTENT_D64 1
 #endif
 
+// 1: the d = 64 kernels are compiled for two resident workgroups per CU (128 registers per lane).  The one-tile-per-
+// workgroup kernels need 113 registers and are resident in pairs anyway; the persistent causal one needs 168 (the next
+// tile's Q fragments are loaded under the epilogue), and forced down to 128 it spills and gains nothing (measured on
+// MI355X, c2 causal: 552 vs 548-558 TFLOP/s), so the knob is off.
+#ifndef ATTN_D64_TWO_WG
+#define ATTN_D64_TWO_WG 0
+#endif
+
 // Which wave group issues the global -> LDS copies (see COPY_WAVES in the kernel).
 #ifndef ATTN_COPY_GROUP
 #define ATTN_COPY_GROUP 0
@@ -121,8 +129,10 @@ __device__ __forceinline__ float xor32_sum(float x) {
     return a + b;
 }
 
+// (d = 64: the LDS ring is 64 KiB, two workgroups fit a CU; the second launch bound, waves per SIMD, asks the
+// compiler for the 128 registers per lane that let their 16 waves be resident together)
 template <int DTYPE, int D, int NW, int MB, int BN, int STAGES, bool CAUSAL, bool PERSIST>
-__global__ __launch_bounds__(NW * 64)
+__global__ __launch_bounds__(NW * 64, (D == 64 && ATTN_D64_TWO_WG) ? 4 : 1)
 void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                      uint16_t* __restrict__ o, float* __restrict__ lse, int N, int nqt, int total,
                      float scale, float scale_log2e)
