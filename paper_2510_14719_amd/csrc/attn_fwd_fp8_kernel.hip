@@ -80,6 +80,14 @@ constexpr float RESCALE_LOG2_FP8 = 8.0f;
 #define ATTN8_INTERLEAVE 1
 #endif
 
+// 1: the causal launch is persistent (one workgroup per CU walking the static serpentine tile schedule, tile after
+// tile with a barrier in between).  Measured on MI355X (B2 H32 N8192 d128 causal): 1626 TFLOP/s against 1683 with one
+// workgroup per tile: the hardware's own dispatch already overlaps one workgroup's epilogue with the next one's
+// prologue, which this simple form does not, and the tile switch spills.  Off.
+#ifndef ATTN8_PERSISTENT
+#define ATTN8_PERSISTENT 0
+#endif
+
 // 1: in the steady state the copies of a stage are issued inside the pass, one piece behind each of a few
 // MFMAs; 0: all of them right after the barrier.
 #ifndef ATTN8_COPIES_IN_PASS
@@ -107,7 +115,7 @@ __device__ __forceinline__ float xor32_max_fp8(float x) {
     return __builtin_fmaxf(a, b);
 }
 
-template <int OUT, int D, int BN, bool CAUSAL>
+template <int OUT, int D, int BN, bool CAUSAL, bool PERSIST>
 __global__ __launch_bounds__(512)
 void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, const uint8_t* __restrict__ v,
                          uint16_t* __restrict__ o, float* __restrict__ lse, int N, int nqt, int total,
@@ -135,11 +143,18 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
     const unsigned lds_base = (unsigned)(size_t)(LDS_AS void*)smem;
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    const int lr = lane & 31, g = lane >> 5;
 
-    // ---- which (batch*head, query tile) this workgroup works on
-    const int tile = __builtin_amdgcn_readfirstlane(tile_schedule(total, (int)gridDim.x, (int)blockIdx.x, 0));
+    // ---- which (batch*head, query tile) this workgroup works on.  PERSIST (the causal launch): one workgroup per CU
+    // walks the static serpentine schedule of tile_schedule.h round by round (the persistent, statically balanced
+    // launch of the paper's Section 4.2: long and short query tiles are paired); otherwise one round.
+    for (int round = 0;; ++round) {
+    const int tile = __builtin_amdgcn_readfirstlane(tile_schedule(total, (int)gridDim.x, (int)blockIdx.x, round));
+    if (tile < 0) break;
+    // (the lane id is taken afresh in every round: everything derived from it then belongs to the round, and the
+    // compiler does not hoist a dozen per-lane constants out of the loop and spill them)
+    int lane;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
+    const int lr = lane & 31, g = lane >> 5;
     const int bh = __builtin_amdgcn_readfirstlane(tile / nqt);
     int qt = tile - bh * nqt;
     if (CAUSAL) qt = nqt - 1 - qt;              // long rows first
@@ -534,6 +549,9 @@ void attn_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restric
                 }
         }
     }
+    if (!PERSIST) break;
+    __builtin_amdgcn_s_barrier();               // every wave is done reading the ring before the next tile's copies go out
+    }   // rounds
 #ifdef ATTN8_TIMING
     if (blockIdx.x < DBG8_WGS && lane == 0) {
         unsigned long long* d = attn8_dbg + (blockIdx.x * 8 + wave) * DBG8_SLOTS;
@@ -553,16 +571,24 @@ extern "C" int attn8_dbg_read(unsigned long long* host, int n)
 namespace {
 #endif
 
-template <int OUT, int D, int BN, bool CAUSAL>
+template <int OUT, int D, int BN, bool CAUSAL, bool PERSIST>
 int launch_fp8(const AttnLaunchArgs& a)
 {
     constexpr int BM = 256;
     constexpr int smem = ATTN8_STAGES * 2 * BN * D;
-    auto kern = attn_fwd_fp8_kernel<OUT, D, BN, CAUSAL>;
+    auto kern = attn_fwd_fp8_kernel<OUT, D, BN, CAUSAL, PERSIST>;
     static PerDeviceOnce once;                  // the attribute belongs to the (kernel, device) pair
-    if (once.prepare(reinterpret_cast<const void*>(kern), smem) < 0) return -1;
+    const int dev = once.prepare(reinterpret_cast<const void*>(kern), smem);
+    if (dev < 0) return -1;
     const int nqt = (a.N + BM - 1) / BM;
     const long long total = (long long)nqt * a.B * a.H;
+    // Persistent launch: one workgroup per CU (eight waves at two per SIMD fill it), each walking its share of the schedule.
+    long long grid = total;
+    if (PERSIST) {
+        const int cus = once.compute_units(dev);
+        if (cus < 8) return -1;
+        if (grid > cus) grid = cus;
+    }
     const float log2e = 1.4426950408889634f;
     const uint8_t* q = (const uint8_t*)a.q;
     const uint8_t* k = (const uint8_t*)a.k;
@@ -572,7 +598,7 @@ int launch_fp8(const AttnLaunchArgs& a)
     int N = a.N, nqt_arg = nqt, total_arg = (int)total;
     float scale = a.scale, scale_log2e = a.scale * log2e;
     void* args[] = {&q, &k, &v, &o, &lse, &N, &nqt_arg, &total_arg, &scale, &scale_log2e};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3((unsigned)total), dim3(512),
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3((unsigned)grid), dim3(512),
                                          args, smem, (hipStream_t)a.stream);
     return e == hipSuccess ? 0 : -1;
 }
@@ -581,7 +607,8 @@ template <int OUT, int D>
 int launch_fp8_d(const AttnLaunchArgs& a)
 {
     constexpr int BN = D == 128 ? ATTN8_CFG_BN_D128 : ATTN8_CFG_BN_D64;
-    return a.causal ? launch_fp8<OUT, D, BN, true>(a) : launch_fp8<OUT, D, BN, false>(a);
+    if (a.causal) return ATTN8_PERSISTENT ? launch_fp8<OUT, D, BN, true, true>(a) : launch_fp8<OUT, D, BN, true, false>(a);
+    return launch_fp8<OUT, D, BN, false, false>(a);
 }
 
 }  // namespace
