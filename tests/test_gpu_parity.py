@@ -79,8 +79,8 @@ def test_benchmark_configs_sampled_rows(G, oracle, name):
     _sampled(G, oracle, name, 192)
 
 
-# ------------------------------------------------------------ the two largest configurations, whole heads
-@pytest.mark.parametrize("name", ["c4", "c5"])
+# ------------------------------------------------------------ the full-size configurations, whole heads
+@pytest.mark.parametrize("name", ["c2", "c2_causal", "c3", "c4", "c5"])
 def test_whole_heads_of_the_large_configs(G, oracle, name):
     """Full size, the launch configuration ``bench.py`` times: every element of O and LSE was written (the buffers
     start out as NaN), and the first and the last (batch, head) agree with the oracle element by element."""
