@@ -148,12 +148,13 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int RB = BN / 16;                 // 16-row blocks per tile
     constexpr int CHUNKS = TILE_BYTES / 1024;   // 1 KiB wave-transfers per tile
     // Which waves issue the copies: 0 = all eight, 1 = group B only, 2 = group A only.
-    constexpr int COPY_WAVES = ATTN_COPY_GROUP == 0 ? NW : NW / 2;
+    constexpr int NG = NW / 4;                  // wave groups: one wave of each group per SIMD
+    constexpr int COPY_WAVES = NG == 3 ? 8 : (ATTN_COPY_GROUP == 0 ? NW : NW / 2);
     constexpr int CPW = CHUNKS / COPY_WAVES;    // ... per copying wave
     constexpr int LPG = 2 * CPW;                // copies such a wave issues per stage (K part + V part)
     static_assert(CHUNKS % COPY_WAVES == 0, "tile must split evenly over the copying waves");
     static_assert(STAGES == 4, "the ring protocol below keeps four stages");
-    static_assert(NW == 8, "two groups of four waves, one wave of each group per SIMD");
+    static_assert(NW == 8 || NW == 12, "two or three groups of four waves, one wave of each group per SIMD");
 
 #ifdef ATTN_TIMING
     const unsigned long long rt_kernel_entry = __builtin_amdgcn_s_memrealtime();
@@ -164,7 +165,8 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in an SGPR
     const int lane = threadIdx.x & 63;
     const int lr = lane & 31, g = lane >> 5;
-    const bool group_b = wave >= NW / 2;        // waves w and w + 4 share a SIMD
+    const int group = __builtin_amdgcn_readfirstlane(wave >> 2);   // waves w, w + 4 (, w + 8) share a SIMD
+    const bool group_b = group == NG - 1;       // the group that does its softmax first
 
     // ---- which (batch*head, query tile) the workgroup works on: set per round of the tile schedule
     int round = 0;
@@ -210,8 +212,9 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // sequence (their surplus rows are masked or never read).
     const unsigned k_lane_off = (lane & 15) * ROW_BYTES + (lane >> 4) * 16;
     const unsigned v_lane_off = (lane >> 2) * ROW_BYTES + (lane & 3) * 16;
-    const bool copies = ATTN_COPY_GROUP == 0 || (ATTN_COPY_GROUP == 1) == group_b;   // does this wave issue copies
-    const int cwave = ATTN_COPY_GROUP == 0 ? wave : (wave & (NW / 2 - 1));         // its index among the copying waves
+    // does this wave issue copies, and its index among the copying waves (three groups: the first eight waves)
+    const bool copies = NG == 3 ? wave < 8 : (ATTN_COPY_GROUP == 0 || (ATTN_COPY_GROUP == 1) == group_b);
+    const int cwave = (NG == 3 || ATTN_COPY_GROUP == 0) ? wave : (wave & (NW / 2 - 1));
     int piece_src[CPW], piece_dst[CPW];         // wave-uniform: source offset inside a tile, LDS offset inside a K or V slot
 #pragma unroll
     for (int i = 0; i < CPW; ++i) {
@@ -339,12 +342,16 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // that factor), so the rescaling of O is rare after the first tiles.
     // With `spread` the wave's copies of stage j + 2 (known to lie inside the sequence) go out between the
     // exponentials, evenly spaced.
-    auto softmax_tile = [&](int j, auto spread) __attribute__((always_inline)) {
+    // `part`: 0 = the whole tile; 1 = mask, maximum, reference, rescaling and the first half of the score pairs;
+    // 2 = the second half of the pairs and the row sum (the middle group of three splits its softmax around its burst).
+    float part_negmc[MB], part_sum[MB][ATTN_SUMCHAINS];
+    auto softmax_tile = [&](int j, auto spread, auto part) __attribute__((always_inline)) {
         constexpr bool SPREAD = decltype(spread)::value;
+        constexpr int PART = decltype(part)::value;
         constexpr int NPAIR = KB * 8, NCOPY = 2 * CPW, PER = NPAIR / NCOPY;
         static_assert(!SPREAD || (PER >= 1 && PER * NCOPY == NPAIR), "copies spread evenly over the exponentials");
         const int kv0 = j * BN;
-        if ((kv0 + BN > N) || (CAUSAL && kv0 + BN - 1 > wq0)) {
+        if (PART != 2 && ((kv0 + BN > N) || (CAUSAL && kv0 + BN - 1 > wq0))) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 const int qi = wq0 + mb * 32 + lr;
@@ -362,29 +369,38 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         bool upd_any = false;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            float mx = S[mb][0][0];
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = __builtin_fmaxf(mx, S[mb][kb][i]);
-            mx = xor32_max(mx);
-            const float m_old = m_run[mb];
-            const float m_new = __builtin_fmaxf(m_old, mx);
-            const bool upd = (m_new - m_old) * scale_log2e > RESCALE_LOG2;
-            const float m_use = upd ? m_new : m_old;
-            upd_any |= upd;
-            alpha[mb] = __builtin_amdgcn_exp2f((m_old - m_use) * scale_log2e);
-            const float neg_mc = -m_use * scale_log2e;
-            m_run[mb] = m_use;
             // independent chains: a dot2 accumulate has a dependent latency of about four issue slots
             constexpr int NCH = ATTN_SUMCHAINS;
             float sum[NCH];
+            float neg_mc;
+            alpha[mb] = 1.0f;
+            if (PART != 2) {
+                float mx = S[mb][0][0];
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) sum[c] = 0.f;
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) mx = __builtin_fmaxf(mx, S[mb][kb][i]);
+                mx = xor32_max(mx);
+                const float m_old = m_run[mb];
+                const float m_new = __builtin_fmaxf(m_old, mx);
+                const bool upd = (m_new - m_old) * scale_log2e > RESCALE_LOG2;
+                const float m_use = upd ? m_new : m_old;
+                upd_any |= upd;
+                alpha[mb] = __builtin_amdgcn_exp2f((m_old - m_use) * scale_log2e);
+                neg_mc = -m_use * scale_log2e;
+                m_run[mb] = m_use;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) sum[c] = 0.f;
+            } else {
+                neg_mc = part_negmc[mb];
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) sum[c] = part_sum[mb][c];
+            }
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
+                    if ((PART == 1 && kb * 8 + t >= NPAIR / 2) || (PART == 2 && kb * 8 + t < NPAIR / 2)) continue;
                     const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][kb][2 * t], scale_log2e, neg_mc));
                     const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][kb][2 * t + 1], scale_log2e, neg_mc));
                     const unsigned w = E::pack2(p0, p1);
@@ -396,12 +412,19 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
-            float tile_sum = sum[0];
+            if (PART == 1) {                    // the second half continues these sums with this reference
+                part_negmc[mb] = neg_mc;
 #pragma unroll
-            for (int c = 1; c < NCH; ++c) tile_sum += sum[c];
-            l_run[mb] = l_run[mb] * alpha[mb] + tile_sum;
+                for (int c = 0; c < NCH; ++c) part_sum[mb][c] = sum[c];
+                l_run[mb] = l_run[mb] * alpha[mb];
+            } else {
+                float tile_sum = sum[0];
+#pragma unroll
+                for (int c = 1; c < NCH; ++c) tile_sum += sum[c];
+                l_run[mb] = l_run[mb] * alpha[mb] + tile_sum;
+            }
         }
-        if (__builtin_amdgcn_ballot_w64(upd_any) != 0) {
+        if (PART != 2 && __builtin_amdgcn_ballot_w64(upd_any) != 0) {
             // whole-vector multiplies: element-wise updates would make the compiler split the
             // accumulator tuples into scalars and re-assemble them around every MFMA
 #pragma unroll
@@ -494,12 +517,40 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 #endif
     // Each group's steady state is one loop with a single code path (the first and last tile and the
     // idle tail of a causal wave are peeled off), so the accumulators stay in place across iterations.
-    if (!group_b) {
+    constexpr std::integral_constant<int, 0> WHOLE{};
+    constexpr std::integral_constant<int, 1> FIRST_HALF{};
+    constexpr std::integral_constant<int, 2> SECOND_HALF{};
+    if (NG == 3 && group == 1) {
+        // the middle group of three, iteration j: second half of C_j, then [U_j, T_{j+1}], then the first half of
+        // C_{j+1}; both contractions read stage j.  Its burst falls between those of the first group (right after
+        // the barrier) and of the last (after its whole softmax): three bursts per SIMD and tile, back to back.
+        mfma_burst(std::false_type{}, std::true_type{}, stage_ptr(-1));                  // T_0
+        softmax_tile(0, std::false_type{}, FIRST_HALF);
+        int j = 0;
+        if (j + 1 < nt_w) {
+            do {                                // bottom-tested: see group A
+                wait_stage(j);
+                if (j + 2 < nt) issue_stage(j + 2);
+                softmax_tile(j, std::false_type{}, SECOND_HALF);
+                mfma_burst(std::true_type{}, std::true_type{}, stage_ptr(j));
+                softmax_tile(j + 1, std::false_type{}, FIRST_HALF);
+            } while (++j + 1 < nt_w);
+        }
+        wait_stage(j);                                                                   // j == nt_w - 1
+        if (j + 2 < nt) issue_stage(j + 2);
+        softmax_tile(j, std::false_type{}, SECOND_HALF);
+        mfma_burst(std::true_type{}, std::false_type{}, stage_ptr(j));                   // U of the last tile
+        for (++j; j < nt; ++j) {                                                         // idle tail of a causal wave
+            wait_stage(j);
+            if (j + 2 < nt) issue_stage(j + 2);
+        }
+        finish_tile();
+    } else if (!group_b) {
         // group A, iteration j: [U_{j-1}, T_j] then C_j; both contractions read stage j-1
         wait_stage(0);
         mfma_burst(std::false_type{}, std::true_type{}, stage_ptr(-1));                  // T_0
         if (2 < nt) issue_stage(2);
-        softmax_tile(0, std::false_type{});
+        softmax_tile(0, std::false_type{}, WHOLE);
         auto iter_a = [&](int j, auto spread) __attribute__((always_inline)) {
             TSTAMP(t0);
             wait_stage(j);
@@ -508,7 +559,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             TSTAMP(t2);
             if (!decltype(spread)::value && j + 2 < nt) issue_stage(j + 2);
             TSTAMP(t3);
-            softmax_tile(j, spread);
+            softmax_tile(j, spread, WHOLE);
             TSTAMP(t4);
             TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3); TACC(3, t3, t4);
         };
@@ -545,7 +596,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             TSTAMP(t1);
             if (!decltype(spread)::value && j + 2 < nt) issue_stage(j + 2);
             TSTAMP(t2);
-            softmax_tile(j, spread);
+            softmax_tile(j, spread, WHOLE);
             TSTAMP(t3);
             mfma_burst(std::true_type{}, std::true_type{}, stage_ptr(j));
             TSTAMP(t4);
@@ -565,7 +616,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         }
         wait_stage(j);                                                                   // j == nt_w - 1
         if (j + 2 < nt) issue_stage(j + 2);
-        softmax_tile(j, std::false_type{});
+        softmax_tile(j, std::false_type{}, WHOLE);
         mfma_burst(std::true_type{}, std::false_type{}, stage_ptr(j));                   // U of the last tile
         for (++j; j < nt; ++j) {                                                         // idle tail of a causal wave
             wait_stage(j);
@@ -633,7 +684,7 @@ int launch(const AttnLaunchArgs& a)
 template <int DTYPE, int D>
 int launch_d(const AttnLaunchArgs& a)
 {
-    constexpr int NW = ATTN_CFG_NW, MB = D == 64 ? ATTN_CFG_MB_D64 : ATTN_CFG_MB, BN = ATTN_CFG_BN, STAGES = ATTN_CFG_STAGES;
+    constexpr int NW = D == 128 ? ATTN_CFG_NW : 8, MB = D == 64 ? ATTN_CFG_MB_D64 : ATTN_CFG_MB, BN = ATTN_CFG_BN, STAGES = ATTN_CFG_STAGES;
     // When the persistent form is used (d = 128 only: at d = 64 two workgroups share a CU and cover each
     // other's prologue and epilogue, and the next tile's Q fragments would cost the registers that let
     // them co-reside).  Causal: always; measured +2.5 % at N = 8192 (balanced tile lengths, next
@@ -678,10 +729,10 @@ int attn_launch_tile_param(int d, int causal, int which)
         }
     }
     switch (which) {
-        case 0: return ATTN_CFG_NW * (d == 64 ? ATTN_CFG_MB_D64 : ATTN_CFG_MB) * 32;
+        case 0: return (d == 128 ? ATTN_CFG_NW : 8) * (d == 64 ? ATTN_CFG_MB_D64 : ATTN_CFG_MB) * 32;
         case 1: return ATTN_CFG_BN;
         case 2: return ATTN_CFG_STAGES;
-        case 3: return ATTN_CFG_NW * 64;
+        case 3: return (d == 128 ? ATTN_CFG_NW : 8) * 64;
         default: return -1;
     }
 }

@@ -3,7 +3,7 @@
 
 // Tile configuration compiled into the library.
 #ifndef ATTN_CFG_NW
-#define ATTN_CFG_NW 8        // waves per workgroup
+#define ATTN_CFG_NW 8        // waves per workgroup at d = 128: 8 (two wave groups) or 12 (three); d = 64 always 8
 #endif
 #ifndef ATTN_CFG_MB
 #define ATTN_CFG_MB 1        // 32-query blocks per wave at d = 128

@@ -26,6 +26,10 @@ What the axes stand for on gfx950:
              The 16-bit two-group kernel fixes its ring depth (4 stages: the protocol and the 160 KiB LDS), its tile
              (64 keys) and its eight waves by construction (static_asserts in the source); the in-wave kernel is
              the variant with another ring (5 stages) and, as ATTNP_CFG_NW = 4, with four waves of 64 rows.
+  attn_waves ATTN_CFG_NW        waves per workgroup of the two-group kernel: 8 (two groups, 256 query rows) or 12 (THREE groups
+                                of four waves, one wave of each per SIMD, 384 query rows, 168 registers per wave: the
+                                middle group splits its softmax around its burst, so that a SIMD sees three bursts per
+                                tile back to back)
   attention  ATTN_FWIN          LDS fragments requested ahead of their MFMA inside a burst (the paper's P)
              ATTN_COPY_GROUP    which waves produce (issue the global -> LDS copies): 0 all, 2 group A, 1 group B
              ATTN_SUMCHAINS     independent row-sum chains of the softmax
@@ -60,13 +64,14 @@ VARIANT_DIR = os.path.join(HERE, "sweep_variants")
 
 GRIDS = {
     "attn_schedule": {"ATTN_CFG_PIPE": [0, 1], "ATTNP_CFG_NW": [8, 4], "ATTNP_INTERLEAVE": [1, 0], "ATTNP_FWIN": [3, 2]},
+    "attn_waves": {"ATTN_CFG_NW": [8, 12]},
     "attn": {"ATTN_FWIN": [1, 2, 4, 8], "ATTN_COPY_GROUP": [0, 2, 1], "ATTN_SUMCHAINS": [2, 4]},
     "attn_causal": {"ATTN_PERSISTENT": [0, 1], "ATTN_FWIN": [2, 4]},
     "attn_fp8": {"ATTN8_FWIN": [1, 2, 3], "ATTN8_INTERLEAVE": [1, 0], "ATTN8_STAGES": [4, 8], "ATTN8_COPIES_IN_PASS": [1, 0]},
     "gemm": {"GEMM_CONFIG": [0, 1, 2, 3, 4], "GEMM_STAGES": [4, 5], "GEMM_TAIL_READS": [3, 0]},
     "gemm_fp8": {"GEMM8_CONFIG": [0, 1, 2, 3, 4], "GEMM8_STAGES": [4, 5], "GEMM8_TAIL_READS": [3, 0]},
 }
-DEFAULTS = {"ATTN_CFG_PIPE": 0, "ATTNP_CFG_NW": 8, "ATTNP_INTERLEAVE": 1, "ATTNP_FWIN": 3, "ATTN8_FWIN": 2, "ATTN8_INTERLEAVE": 1, "ATTN8_STAGES": 4, "ATTN8_COPIES_IN_PASS": 1, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
+DEFAULTS = {"ATTN_CFG_NW": 8, "ATTN_CFG_PIPE": 0, "ATTNP_CFG_NW": 8, "ATTNP_INTERLEAVE": 1, "ATTNP_FWIN": 3, "ATTN8_FWIN": 2, "ATTN8_INTERLEAVE": 1, "ATTN8_STAGES": 4, "ATTN8_COPIES_IN_PASS": 1, "ATTN_FWIN": 2, "ATTN_COPY_GROUP": 0, "ATTN_SUMCHAINS": 4, "ATTN_PERSISTENT": 1,
             "GEMM_STAGES": 4, "GEMM_CONFIG": 0, "GEMM_TAIL_READS": 3,
             "GEMM8_STAGES": 4, "GEMM8_TAIL_READS": 3, "GEMM8_COPY_PHASE": 1, "GEMM8_CONFIG": 0}
 
@@ -76,6 +81,7 @@ TEST_VARIANTS = {
     "attn_schedule": [{"ATTN_CFG_PIPE": 1, "ATTNP_CFG_NW": 8, "ATTNP_INTERLEAVE": 1, "ATTNP_FWIN": 3},
                       {"ATTN_CFG_PIPE": 1, "ATTNP_CFG_NW": 8, "ATTNP_INTERLEAVE": 0, "ATTNP_FWIN": 2},
                       {"ATTN_CFG_PIPE": 1, "ATTNP_CFG_NW": 4, "ATTNP_INTERLEAVE": 1, "ATTNP_FWIN": 3}],
+    "attn_waves": [{"ATTN_CFG_NW": 12}],
     "attn": [{"ATTN_FWIN": 4, "ATTN_COPY_GROUP": 2, "ATTN_SUMCHAINS": 2}, {"ATTN_FWIN": 1, "ATTN_COPY_GROUP": 1, "ATTN_SUMCHAINS": 4}],
     "attn_causal": [{"ATTN_PERSISTENT": 0, "ATTN_FWIN": 2}, {"ATTN_PERSISTENT": 1, "ATTN_FWIN": 4}],
     "attn_fp8": [{"ATTN8_FWIN": 3, "ATTN8_INTERLEAVE": 0, "ATTN8_STAGES": 4, "ATTN8_COPIES_IN_PASS": 1},
@@ -194,7 +200,7 @@ def cmd_run(args) -> int:
                                                 w.B, w.H, w.N, w.d, w.scale, int(w.causal), stream, 0)
             view = lambda: np.concatenate([out.view(torch.float16)[:, :, ::251, ::7].float().cpu().numpy().ravel(),
                                            lse[:, :, ::251].cpu().numpy().ravel()])
-        else:               # attn, attn_causal, attn_schedule
+        else:               # attn, attn_causal, attn_schedule, attn_waves
             w = I.WORKLOADS[args.causal_workload if op == "attn_causal" else args.workload]
             q, k, v = (torch.from_numpy(x.view("int16")).cuda() for x in I.make_workload(w))
             out = torch.empty_like(q)

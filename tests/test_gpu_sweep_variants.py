@@ -63,7 +63,7 @@ def _check(of, lf, o_ref, l_ref, what, tol=(TOL_O_MAX, TOL_O_MEAN, TOL_LSE)):
     assert eo.max() <= tol[0] and eo.mean() <= tol[1] and el.max() <= tol[2], msg
 
 
-@pytest.mark.parametrize("op,point", _cases("attn_schedule") + _cases("attn") + _cases("attn_causal"))
+@pytest.mark.parametrize("op,point", _cases("attn_schedule") + _cases("attn_waves") + _cases("attn") + _cases("attn_causal"))
 def test_attention_variants_against_the_oracle(env, op, point):
     torch, oracle, _ = env
     lib = _lib(op, point)
