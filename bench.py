@@ -32,7 +32,7 @@ DTYPE_NAME = {0: "fp16", 1: "bf16", 2: "fp8-e4m3"}
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each scaled by what the
 # counter reads for a 1 GiB copy): a profile's figure, not measured by this script.  Every summary under
 # profiles/ that holds such a measurement carries one line "TRAFFIC_BYTES_PER_LAUNCH = <bytes>".
-PROFILE_OF = {"c4": "profiles/attn_fwd_c4_fp16_noncausal.md", "c5": "profiles/attn_fwd_c5_bf16_causal.md",
+PROFILE_OF = {"c4": "profiles/attn_fwd_c4_fp16_noncausal.md", "c3": "profiles/attn_fwd_c3_bf16_noncausal.md", "c5": "profiles/attn_fwd_c5_bf16_causal.md",
               "c2": "profiles/attn_fwd_c2_fp16_d64_noncausal.md", "c2_causal": "profiles/attn_fwd_c2_fp16_d64_causal.md",
               "f4": "profiles/attn_fwd_fp8_f4_e4m3_noncausal.md",
               ("gemm", 16384): "profiles/gemm_nt_m8192_n8192_k16384_fp16.md",
